@@ -1,0 +1,140 @@
+/*
+ * libppow -- window-level scoring pass of PPOW drafter optimisation on AMD MI355X
+ * (gfx950), as a C-ABI library.
+ *
+ * For B speculative windows of K drafted tokens it streams the paired drafter
+ * and target logit rows once and returns, per window, the verification outcome
+ * (accepted prefix length), the Cost-Aware Speedup Reward, the Distribution-Based
+ * Proximity Reward and the ADAW priority score; a second entry point selects the
+ * M windows of largest score.  All data pointers are DEVICE pointers owned by
+ * the caller; the library neither allocates, frees nor keeps them.  The params /
+ * outputs structs are HOST structs read during the call.  Calls enqueue work on
+ * `hip_stream` (a hipStream_t cast to void*; NULL = the default stream) and
+ * return without synchronising: outputs are valid once the stream has drained.
+ * Results are deterministic run to run (no floating-point atomics).
+ *
+ * Every entry point returns a ppow_status.  Errors that the host can see are
+ * reported before anything is launched; ppow_last_error() then holds a message.
+ */
+#ifndef PPOW_H
+#define PPOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PPOW_OK = 0,
+    PPOW_ERR_INVALID_ARG = 1,  /* NULL required pointer, size or enum out of range */
+    PPOW_ERR_UNSUPPORTED = 2,  /* valid request outside the built limits           */
+    PPOW_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or too small          */
+    PPOW_ERR_DEVICE = 4        /* a HIP launch reported an error                   */
+} ppow_status;
+
+/* Storage type of both logit tensors. */
+typedef enum { PPOW_F32 = 0, PPOW_BF16 = 1 } ppow_dtype;
+
+/* Verification rule.  REJECTION: position t is accepted iff u_t <= alpha_t with
+ * alpha_t = min(1, P_t(tok)/Q_t(tok)) (Appendix C.1).  GREEDY: accepted iff the
+ * drafted token is the target's argmax, the temperature-0 limit of the same rule
+ * (Table 5 lists temperature 0.0 among the decoding settings). */
+typedef enum { PPOW_VERIFY_REJECTION = 0, PPOW_VERIFY_GREEDY = 1 } ppow_verify;
+
+enum {
+    /* also compute sum_y min(P_t(y), Q_t(y)), the expected acceptance probability
+     * of Appendix B.1; it needs normalised probabilities, hence a second pass over
+     * each row pair (issued right after the first so that it is served by cache) */
+    PPOW_FLAG_EXPECTED_ACCEPT = 1u
+};
+
+#define PPOW_MAX_K 64          /* drafted positions per window (one wavefront) */
+
+typedef struct {
+    float cost_ratio;  /* gamma > 0: drafter cost relative to the target (Section 4.3.1) */
+    float prox_eps;    /* epsilon: proximity tolerance, Table 5 default 0.5             */
+    float prox_eta;    /* eta: proximity reward scale, Table 5 default 1.0              */
+    int32_t verify;    /* ppow_verify                                                   */
+    uint32_t flags;    /* PPOW_FLAG_*                                                   */
+} ppow_params;
+
+/* Device output arrays.  The first four are required; the rest may be NULL. */
+typedef struct {
+    int32_t *accepted_len;   /* [B]   k: accepted prefix length, 0..K (Appendix C.1)          */
+    float *r_speedup;        /* [B]   k / (k*gamma + 1)              (Section 4.3.1)          */
+    float *r_proximity;      /* [B]   eta * [k == 0] * [delta < eps] (Section 4.3.2, Alg. 1)  */
+    float *adaw_score;       /* [B]   (1/K) sum_t C(P_t) KL(P_t||Q_t) (Section 4.2)           */
+    float *delta;            /* [B]   proximity gap                  (Section 4.3.2)          */
+    float *kl;               /* [B*K] KL(P_t || Q_t) in nats                                  */
+    float *confidence;       /* [B*K] C(P_t) = 1 - H(P_t)/ln V                                */
+    float *accept_prob;      /* [B*K] alpha_t                                                 */
+    float *expected_accept;  /* [B*K] sum_y min(P_t, Q_t); needs PPOW_FLAG_EXPECTED_ACCEPT    */
+    float *logp_target_tok;  /* [B*K] log P_t(drafted token)                                  */
+    float *logp_draft_tok;   /* [B*K] log Q_t(drafted token)                                  */
+} ppow_outputs;
+
+/* Bytes of device workspace ppow_score_windows needs for these sizes (0 on
+ * invalid sizes).  The workspace must be 16-byte aligned. */
+size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype, uint32_t flags);
+
+/*
+ * Score B windows (Algorithm 1: criticality and window score, Verify, proximity
+ * gap and reward lines).
+ *
+ *   draft_logits, target_logits  [B, K, V] dense row-major, V contiguous, `dtype`
+ *                                storage, base pointers 16-byte aligned.  Logits
+ *                                must be finite.  P_t = softmax(target row),
+ *                                Q_t = softmax(draft row), temperature 1.
+ *   draft_tokens                 [B, K] int32, 0 <= token < V (precondition, not
+ *                                checked on the device)
+ *   uniforms                     [B, K] float32 draws u_t in [0,1]; may be NULL
+ *                                only for PPOW_VERIFY_GREEDY
+ *   ref_logprob                  [B] float32 or NULL.  When given it is the
+ *                                cumulative target log-probability of the
+ *                                target-preferred reference window, the first
+ *                                term of the proximity gap of Section 4.3.2.
+ *                                When NULL the reference token of position t is
+ *                                the argmax of the same target row, so that
+ *                                delta = sum_t (max_y a_t[y] - a_t[tok_t]).
+ *   B >= 0 (B = 0 is a no-op), 1 <= K <= PPOW_MAX_K, 2 <= V < 2^31.
+ *
+ * The ADAW score averages over all K positions whether or not verification
+ * stopped earlier.  r_proximity is the gated value that enters the window
+ * reward; the caller adds r_speedup + r_proximity.
+ */
+int ppow_score_windows(const void *draft_logits, const void *target_logits,
+                       const int32_t *draft_tokens, const float *uniforms,
+                       const float *ref_logprob,
+                       int64_t B, int32_t K, int64_t V, int32_t dtype,
+                       const ppow_params *params, const ppow_outputs *out,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device workspace ppow_select_windows needs (0 on invalid sizes). */
+size_t ppow_select_workspace_bytes(int64_t B, int32_t M);
+
+/*
+ * Top-M window selection (Section 4.2: windows with larger score are
+ * prioritised).  Writes the indices of the M largest scores ordered by score
+ * descending, equal scores by index ascending.
+ *
+ *   adaw_score  [B] float32, finite
+ *   indices     [M] int32 out
+ *   scores      [M] float32 out or NULL: the selected scores in the same order
+ *   1 <= M <= B < 2^31.
+ */
+int ppow_select_windows(const float *adaw_score, int64_t B, int32_t M,
+                        int32_t *indices, float *scores,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Message of the calling thread's most recent failed call (static storage). */
+const char *ppow_last_error(void);
+
+/* Library version, "major.minor.patch". */
+const char *ppow_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

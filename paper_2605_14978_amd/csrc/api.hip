@@ -1,0 +1,149 @@
+// C-ABI entry points of libppow: host-side validation and kernel launches.
+// Nothing here allocates device memory or synchronises.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "ppow_device.h"
+
+#include <math.h>
+
+namespace {
+
+thread_local char g_error[256] = "";
+
+int fail(ppow_status code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool sizes_ok(int64_t B, int32_t K, int64_t V, int32_t dtype) {
+    if (B < 0 || K < 1 || K > PPOW_MAX_K || V < 2 || V > INT32_MAX) return false;
+    if (dtype != PPOW_F32 && dtype != PPOW_BF16) return false;
+    if (B > INT32_MAX / K) return false;            // B*K positions are indexed with 32 bits
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ppow_last_error(void) { return g_error; }
+
+const char *ppow_version(void) { return "0.1.0"; }
+
+size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype, uint32_t flags) {
+    (void)flags;
+    if (!sizes_ok(B, K, V, dtype)) return 0;
+    const size_t bytes = static_cast<size_t>(B) * static_cast<size_t>(K) * sizeof(ppow::RowRecord);
+    return bytes < 256 ? 256 : bytes;
+}
+
+int ppow_score_windows(const void *draft_logits, const void *target_logits,
+                       const int32_t *draft_tokens, const float *uniforms,
+                       const float *ref_logprob, int64_t B, int32_t K, int64_t V, int32_t dtype,
+                       const ppow_params *params, const ppow_outputs *out, void *workspace,
+                       size_t workspace_bytes, void *hip_stream) {
+    if (!params || !out) return fail(PPOW_ERR_INVALID_ARG, "params and out must not be NULL");
+    if (!sizes_ok(B, K, V, dtype))
+        return fail(PPOW_ERR_INVALID_ARG,
+                    "sizes out of range: B=%lld K=%d V=%lld dtype=%d (need B>=0, 1<=K<=%d, "
+                    "2<=V<2^31, B*K<2^31, dtype f32|bf16)",
+                    (long long)B, K, (long long)V, dtype, PPOW_MAX_K);
+    if (params->verify != PPOW_VERIFY_REJECTION && params->verify != PPOW_VERIFY_GREEDY)
+        return fail(PPOW_ERR_INVALID_ARG, "unknown verify mode %d", params->verify);
+    if (params->flags & ~static_cast<uint32_t>(PPOW_FLAG_EXPECTED_ACCEPT))
+        return fail(PPOW_ERR_INVALID_ARG, "unknown flag bits 0x%x", params->flags);
+    if (!(params->cost_ratio > 0.f) || !isfinite(params->cost_ratio))
+        return fail(PPOW_ERR_INVALID_ARG, "cost_ratio must be a positive finite number");
+    if (!isfinite(params->prox_eps) || !isfinite(params->prox_eta))
+        return fail(PPOW_ERR_INVALID_ARG, "prox_eps and prox_eta must be finite");
+    if (!draft_logits || !target_logits || !draft_tokens)
+        return fail(PPOW_ERR_INVALID_ARG, "logits and draft_tokens must not be NULL");
+    if (!aligned16(draft_logits) || !aligned16(target_logits))
+        return fail(PPOW_ERR_INVALID_ARG, "logit base pointers must be 16-byte aligned");
+    if (params->verify == PPOW_VERIFY_REJECTION && !uniforms)
+        return fail(PPOW_ERR_INVALID_ARG, "uniforms must be given for rejection verification");
+    if (!out->accepted_len || !out->r_speedup || !out->r_proximity || !out->adaw_score)
+        return fail(PPOW_ERR_INVALID_ARG,
+                    "accepted_len, r_speedup, r_proximity and adaw_score outputs are required");
+    const bool second_pass = (params->flags & PPOW_FLAG_EXPECTED_ACCEPT) != 0;
+    if (out->expected_accept && !second_pass)
+        return fail(PPOW_ERR_INVALID_ARG,
+                    "expected_accept output needs PPOW_FLAG_EXPECTED_ACCEPT");
+    if (second_pass && !out->expected_accept)
+        return fail(PPOW_ERR_INVALID_ARG,
+                    "PPOW_FLAG_EXPECTED_ACCEPT needs the expected_accept output");
+    const size_t need = ppow_score_workspace_bytes(B, K, V, dtype, params->flags);
+    if (!workspace || !aligned16(workspace) || workspace_bytes < need)
+        return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
+    if (B == 0) return PPOW_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t rows = B * K;
+
+    ppow::RowArgs ra;
+    ra.target = target_logits;
+    ra.draft = draft_logits;
+    ra.tokens = draft_tokens;
+    ra.uniforms = uniforms;
+    ra.records = static_cast<ppow::RowRecord *>(workspace);
+    ra.kl = out->kl;
+    ra.confidence = out->confidence;
+    ra.accept_prob = out->accept_prob;
+    ra.expected_accept = out->expected_accept;
+    ra.logp_target_tok = out->logp_target_tok;
+    ra.logp_draft_tok = out->logp_draft_tok;
+    ra.V = V;
+    ra.inv_ln_V = 1.0 / log(static_cast<double>(V));
+    ra.greedy = params->verify == PPOW_VERIFY_GREEDY;
+    ra.second_pass = second_pass;
+    hipError_t err = ppow::launch_row_stats(ra, rows, dtype, stream);
+    if (err != hipSuccess)
+        return fail(PPOW_ERR_DEVICE, "row kernel launch failed: %s", hipGetErrorString(err));
+
+    ppow::WindowArgs wa;
+    wa.records = ra.records;
+    wa.ref_logprob = ref_logprob;
+    wa.accepted_len = out->accepted_len;
+    wa.r_speedup = out->r_speedup;
+    wa.r_proximity = out->r_proximity;
+    wa.adaw_score = out->adaw_score;
+    wa.delta = out->delta;
+    wa.B = B;
+    wa.K = K;
+    wa.cost_ratio = params->cost_ratio;
+    wa.prox_eps = params->prox_eps;
+    wa.prox_eta = params->prox_eta;
+    err = ppow::launch_window_epilogue(wa, stream);
+    if (err != hipSuccess)
+        return fail(PPOW_ERR_DEVICE, "window kernel launch failed: %s", hipGetErrorString(err));
+    return PPOW_OK;
+}
+
+size_t ppow_select_workspace_bytes(int64_t B, int32_t M) {
+    if (B < 1 || B > INT32_MAX || M < 1 || M > B) return 0;
+    return ppow::select_workspace_bytes(B, M);
+}
+
+int ppow_select_windows(const float *adaw_score, int64_t B, int32_t M, int32_t *indices,
+                        float *scores, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (B < 1 || B > INT32_MAX || M < 1 || M > B)
+        return fail(PPOW_ERR_INVALID_ARG, "need 1 <= M <= B < 2^31 (B=%lld, M=%d)", (long long)B, M);
+    if (!adaw_score || !indices)
+        return fail(PPOW_ERR_INVALID_ARG, "adaw_score and indices must not be NULL");
+    const size_t need = ppow::select_workspace_bytes(B, M);
+    if (!workspace || !aligned16(workspace) || workspace_bytes < need)
+        return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
+    const hipError_t err = ppow::launch_select(adaw_score, B, M, indices, scores, workspace,
+                                               static_cast<hipStream_t>(hip_stream));
+    if (err != hipSuccess)
+        return fail(PPOW_ERR_DEVICE, "select kernel launch failed: %s", hipGetErrorString(err));
+    return PPOW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,58 @@
+// Internal declarations shared by the HIP translation units of libppow.
+// Not part of the public interface (that is include/ppow.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ppow.h"
+
+namespace ppow {
+
+// What the row kernel leaves for the window epilogue: one record per (window, position).
+struct RowRecord {
+    float criticality;   // v_t = C(P_t) * KL(P_t || Q_t)            (Section 4.2)
+    float gap;           // max_y a_t[y] - a_t[tok_t]                 (Section 4.3.2, same-context reference)
+    float logp_tok;      // log P_t(tok_t)
+    int32_t accept;      // verification outcome of this position     (Appendix C.1)
+};
+
+struct RowArgs {
+    const void *target;          // [rows, V]
+    const void *draft;           // [rows, V]
+    const int32_t *tokens;       // [rows]
+    const float *uniforms;       // [rows] or nullptr (greedy)
+    RowRecord *records;          // [rows]
+    float *kl;                   // optional per-row outputs, nullptr = skip
+    float *confidence;
+    float *accept_prob;
+    float *expected_accept;
+    float *logp_target_tok;
+    float *logp_draft_tok;
+    int64_t V;
+    double inv_ln_V;             // 1 / ln V
+    int32_t greedy;              // 1: accept iff token == argmax target
+    int32_t second_pass;         // 1: compute sum_y min(P, Q)
+};
+
+struct WindowArgs {
+    const RowRecord *records;    // [B*K]
+    const float *ref_logprob;    // [B] or nullptr
+    int32_t *accepted_len;       // [B]
+    float *r_speedup;            // [B]
+    float *r_proximity;          // [B]
+    float *adaw_score;           // [B]
+    float *delta;                // [B] or nullptr
+    int64_t B;
+    int32_t K;
+    float cost_ratio, prox_eps, prox_eta;
+};
+
+hipError_t launch_row_stats(const RowArgs &args, int64_t rows, int32_t dtype, hipStream_t stream);
+hipError_t launch_window_epilogue(const WindowArgs &args, hipStream_t stream);
+
+size_t select_workspace_bytes(int64_t B, int32_t M);
+hipError_t launch_select(const float *score, int64_t B, int32_t M, int32_t *indices, float *scores,
+                         void *workspace, hipStream_t stream);
+
+}  // namespace ppow

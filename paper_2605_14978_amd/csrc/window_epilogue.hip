@@ -1,0 +1,76 @@
+// Window epilogue: from the per-position records of the row kernel to the four
+// per-window outputs.  Lane t of a group of G = 2^ceil(log2 K) consecutive lanes
+// holds position t of one window, so a wavefront carries 64/G windows.
+//   accepted length  k = number of leading accepted positions: the first zero of
+//                    the group's slice of the wavefront ballot (Appendix C.1: the
+//                    sum over n of the product over t <= n of the accept bits)
+//   R_speedup        k / (k*gamma + 1)                          (Section 4.3.1)
+//   delta            sum_t gap_t, or ref - sum_t log P_t(tok_t) (Section 4.3.2)
+//   r_proximity      eta * [k == 0] * [delta < eps]             (Algorithm 1)
+//   ADAW score       (1/K) sum_t v_t over all K positions       (Section 4.2)
+// Sums use a fixed xor-shuffle tree, so results do not depend on scheduling.
+#include "ppow_device.h"
+
+namespace ppow {
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs args, int log2_group) {
+    const int group = 1 << log2_group;
+    const int lane = threadIdx.x & 63;
+    const int64_t gid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t window = gid >> log2_group;
+    const int t = static_cast<int>(gid & (group - 1));
+    const bool active = (window < args.B) && (t < args.K);
+
+    float v = 0.f, gap = 0.f, logp = 0.f;
+    int accept = 0;
+    if (active) {
+        const RowRecord rec = args.records[window * args.K + t];
+        v = rec.criticality;
+        gap = rec.gap;
+        logp = rec.logp_tok;
+        accept = rec.accept;
+    }
+
+    // first rejected position of this window
+    const unsigned long long ballot = __ballot(active && accept != 0);
+    const int group_base = lane & ~(group - 1);
+    unsigned long long bits = ballot >> group_base;
+    unsigned long long rejected = ~bits;
+    if (args.K < 64) rejected |= (1ull << args.K);          // position K always "rejects"
+    const int k = rejected ? __builtin_ctzll(rejected) : 64;
+
+    // fixed-order sums over the group
+    for (int off = group >> 1; off > 0; off >>= 1) {
+        v += __shfl_xor(v, off, 64);
+        gap += __shfl_xor(gap, off, 64);
+        logp += __shfl_xor(logp, off, 64);
+    }
+
+    if (active && t == 0) {
+        const float kf = static_cast<float>(k);
+        const float delta = args.ref_logprob ? (args.ref_logprob[window] - logp) : gap;
+        args.accepted_len[window] = k;
+        args.r_speedup[window] = kf / fmaf(kf, args.cost_ratio, 1.0f);
+        args.r_proximity[window] = (k == 0 && delta < args.prox_eps) ? args.prox_eta : 0.f;
+        args.adaw_score[window] = v / static_cast<float>(args.K);
+        if (args.delta) args.delta[window] = delta;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_window_epilogue(const WindowArgs &args, hipStream_t stream) {
+    if (args.B == 0) return hipSuccess;
+    int log2_group = 0;
+    while ((1 << log2_group) < args.K) ++log2_group;
+    const int64_t threads = args.B << log2_group;
+    const int64_t blocks = (threads + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(window_epilogue_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0,
+                       stream, args, log2_group);
+    return hipGetLastError();
+}
+
+}  // namespace ppow

@@ -1,0 +1,115 @@
+"""Shared helpers of the GPU parity tests: run libppow and the oracle on the same
+stored inputs and compare element by element.
+
+Tolerances (relative, plus an absolute floor for values near zero):
+  fp32 logits 1e-4, bf16 logits 2e-3; floor 1e-6 (times ln V for log-probability sums).
+Integer results (accepted length, argmax-driven decisions, selected indices) are
+compared exactly.
+"""
+import math
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2605_14978_amd as ppow
+
+RTOL = {"f32": 1e-4, "bf16": 2e-3}
+ATOL = 1e-6
+
+PER_POSITION = ("kl", "confidence", "accept_prob", "logp_target_tok", "logp_draft_tok")
+
+
+def dtype_name(t):
+    return "bf16" if t.dtype == torch.bfloat16 else "f32"
+
+
+def run_gpu(d, *, cost_ratio, verify, prox_eps=0.5, prox_eta=1.0, expected_accept=False,
+            ref_logprob=None, optional=None):
+    opt = list(optional if optional is not None else ("delta",) + PER_POSITION)
+    flags = 0
+    if expected_accept:
+        flags |= ppow.PPOW_FLAG_EXPECTED_ACCEPT
+        opt.append("expected_accept")
+    out = ppow.ppow_score_windows(
+        d["draft_logits"], d["target_logits"], d["draft_tokens"], d["uniforms"], ref_logprob,
+        cost_ratio=cost_ratio, prox_eps=prox_eps, prox_eta=prox_eta,
+        verify=ppow.PPOW_VERIFY_GREEDY if verify == "greedy" else ppow.PPOW_VERIFY_REJECTION,
+        flags=flags, optional=tuple(opt))
+    torch.cuda.synchronize()
+    return out
+
+
+def run_oracle(d, *, cost_ratio, verify, prox_eps=0.5, prox_eta=1.0, expected_accept=False,
+               ref_logprob=None):
+    want = list(PER_POSITION)
+    if expected_accept:
+        want.append("expected_accept")
+    u = d["uniforms"]
+    return oracle.score_windows(
+        d["draft_logits"].cpu(), d["target_logits"].cpu(), d["draft_tokens"].cpu().numpy(),
+        None if u is None else u.cpu().numpy(),
+        None if ref_logprob is None else ref_logprob.cpu().numpy(),
+        cost_ratio=cost_ratio, prox_eps=prox_eps, prox_eta=prox_eta,
+        verify=oracle.GREEDY if verify == "greedy" else oracle.REJECTION, want=tuple(want))
+
+
+def assert_close(name, got, ref, rtol, atol=ATOL):
+    got = np.asarray(got, dtype=np.float64).reshape(-1)
+    ref = np.asarray(ref, dtype=np.float64).reshape(-1)
+    assert got.shape == ref.shape, f"{name}: shape {got.shape} vs {ref.shape}"
+    err = np.abs(got - ref)
+    bound = rtol * np.abs(ref) + atol
+    worst = int(np.argmax(err - bound))
+    assert np.all(err <= bound), (
+        f"{name}: element {worst} got {got[worst]!r} ref {ref[worst]!r} "
+        f"err {err[worst]:.3e} > bound {bound[worst]:.3e}")
+
+
+def compare(gpu, ref, dname, V, expected_accept=False):
+    """Element-by-element comparison of one scoring call against the oracle."""
+    rtol = RTOL[dname]
+    assert np.array_equal(gpu.accepted_len.cpu().numpy(), ref.accepted_len), "accepted_len differs"
+    assert_close("r_speedup", gpu.r_speedup.cpu(), ref.r_speedup, rtol)
+    assert np.array_equal(gpu.r_proximity.cpu().numpy().astype(np.float64), ref.r_proximity), \
+        "r_proximity differs"
+    assert_close("adaw_score", gpu.adaw_score.cpu(), ref.adaw_score, rtol)
+    if gpu.delta is not None:
+        assert_close("delta", gpu.delta.cpu(), ref.delta, rtol, ATOL * math.log(V))
+    for name in PER_POSITION:
+        t = getattr(gpu, name)
+        if t is not None:
+            atol = ATOL * math.log(V) if name.startswith("logp") else ATOL
+            assert_close(name, t.cpu(), getattr(ref, name), rtol, atol)
+    if expected_accept:
+        assert_close("expected_accept", gpu.expected_accept.cpu(), ref.expected_accept, rtol)
+
+
+def check_selection(gpu_scores, M, oracle_scores=None, rtol=None):
+    """Selector exactness on the GPU's own fp32 scores, and (optionally) end-to-end
+    agreement with the oracle's scores as sets, up to windows whose oracle score lies
+    within the float tolerance of the M-th / (M+1)-th boundary."""
+    sel = ppow.ppow_select_windows(gpu_scores, M)
+    torch.cuda.synchronize()
+    idx = sel.indices.cpu().numpy().astype(np.int64)
+    s32 = gpu_scores.cpu().numpy()
+    expect = oracle.select_windows(s32.astype(np.float64), M)
+    assert np.array_equal(idx, expect), "selected indices differ from a full stable sort"
+    assert np.array_equal(sel.scores.cpu().numpy(), s32[expect]), "selected scores differ"
+    if oracle_scores is not None:
+        ref_idx = oracle.select_windows(oracle_scores, M)
+        B = oracle_scores.size
+        if M < B:
+            order = np.lexsort((np.arange(B), -oracle_scores))
+            boundary = 0.5 * (oracle_scores[order[M - 1]] + oracle_scores[order[M]])
+            tol = rtol * abs(boundary) + ATOL
+            must = set(np.nonzero(oracle_scores > boundary + tol)[0].tolist())
+            may = set(np.nonzero(oracle_scores >= boundary - tol)[0].tolist())
+            got = set(idx.tolist())
+            assert must <= got <= may, "selection disagrees with the oracle beyond the tolerance band"
+            gap = oracle_scores[order[M - 1]] - oracle_scores[order[M]]
+            if gap > 2 * tol:
+                assert got == set(ref_idx.tolist())
+        else:
+            assert set(idx.tolist()) == set(ref_idx.tolist())
+    return idx
