@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the PPOW window-scoring hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic windows already
+resident in HBM: ppow_score_windows (row-pair streaming reduction + window
+epilogue) followed by ppow_select_windows (top-M).  Prints ONE JSON line with the
+whole-job throughput in windows/s, the roofline figures of the dominant kernel
+(the row-pair streaming reduction, HBM-bound) and the CPU oracle timed on a
+bounded sample of the same inputs.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="rejection_bf16_128k")
+    ap.add_argument("--windows", type=int, default=0,
+                    help="override the window count B (0: the workload's own)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="CPU time budget of the oracle baseline (0 disables it)")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, inputs, gpu_out, seconds):
+    """Time the oracle, as it stands, on the first windows of the same inputs."""
+    import numpy as np
+    import oracle
+
+    def run(n):
+        a = inputs["target_logits"][:n].cpu()
+        b = inputs["draft_logits"][:n].cpu()
+        tok = inputs["draft_tokens"][:n].cpu().numpy()
+        u = inputs["uniforms"]
+        u = None if u is None else u[:n].cpu().numpy()
+        want = ("kl", "confidence", "accept_prob") + (("expected_accept",) if w.expected_accept else ())
+        t0 = time.perf_counter()
+        res = oracle.score_windows(b, a, tok, u, cost_ratio=w.cost_ratio, prox_eps=w.prox_eps,
+                                   prox_eta=w.prox_eta,
+                                   verify=oracle.GREEDY if w.verify == "greedy" else oracle.REJECTION,
+                                   want=want)
+        oracle.select_windows(res.adaw_score, max(1, min(w.M, n)))
+        return res, time.perf_counter() - t0
+
+    probe = min(w.B, 32)
+    res, dt = run(probe)
+    n = int(min(w.B, max(probe, probe * seconds / max(dt, 1e-6))))
+    if n > probe:
+        res, dt = run(n)
+    k_gpu = gpu_out.accepted_len[:n].cpu().numpy()
+    s_gpu = gpu_out.adaw_score[:n].cpu().numpy().astype(np.float64)
+    rtol = 2e-3 if w.dtype == "bf16" else 1e-4
+    agrees = bool(np.array_equal(k_gpu, res.accepted_len) and
+                  np.all(np.abs(s_gpu - res.adaw_score) <= rtol * np.abs(res.adaw_score) + 1e-6))
+    return {"value": n / dt, "unit": "windows/s", "cores": res.threads, "kind": "oracle",
+            "sample": f"first {n} of {w.B} windows of the timed batch, scoring + selection, "
+                      f"{dt:.1f} s", "gpu_matches_oracle_on_sample": agrees}
+
+
+def measured_traffic(name):
+    """HBM bytes per launch of the row kernel from committed rocprofv3 counter runs, if any."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        return json.load(fh).get(name, {}).get("bytes_per_launch")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (windows are independent, so more "
+                 "GPUs would each score their own share); run with --gpus 1")
+    import torch
+    import paper_2605_14978_amd as ppow
+    from workloads import WORKLOADS, generate
+    from workloads.generate import accepted_length_histogram, describe
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    ppow.lib()                                     # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+
+    w = WORKLOADS[args.workload]
+    if args.windows:
+        w = w.scaled(args.windows)
+    print(f"# {describe(w)}", file=sys.stderr, flush=True)
+
+    t0 = time.perf_counter()
+    inputs = generate(w, device=dev)
+    torch.cuda.synchronize()
+    print(f"# generated inputs in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    code = ppow.PPOW_BF16 if w.dtype == "bf16" else ppow.PPOW_F32
+    flags = ppow.PPOW_FLAG_EXPECTED_ACCEPT if w.expected_accept else 0
+    optional = ("expected_accept",) if w.expected_accept else ()
+    sbuf = ppow.ScoreBuffers(w.B, w.K, w.V, code, dev, optional, flags)
+    selbuf = ppow.SelectBuffers(w.B, w.M, dev)
+    verify = ppow.PPOW_VERIFY_GREEDY if w.verify == "greedy" else ppow.PPOW_VERIFY_REJECTION
+
+    def score():
+        ppow.ppow_score_windows(inputs["draft_logits"], inputs["target_logits"],
+                                inputs["draft_tokens"], inputs["uniforms"],
+                                cost_ratio=w.cost_ratio, prox_eps=w.prox_eps, prox_eta=w.prox_eta,
+                                verify=verify, flags=flags, buffers=sbuf)
+
+    def select():
+        ppow.ppow_select_windows(sbuf.adaw_score, w.M, buffers=selbuf)
+
+    for _ in range(args.warmup):
+        score()
+        select()
+    torch.cuda.synchronize()
+
+    # HIP events on the launch stream (torch's current stream) bracket each scoring call:
+    # the row kernel plus the microsecond-scale window epilogue.
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        score()
+        stops[i].record()
+        select()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    score_ms = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
+    algorithmic_bytes = w.B * w.logit_bytes_per_window
+    achieved = algorithmic_bytes / (score_ms * 1e-3) / 1e9
+    hist = accepted_length_histogram(sbuf.accepted_len, w.K)
+    print(f"# accepted-length histogram 0..K: {hist}", file=sys.stderr, flush=True)
+
+    result = {
+        "metric": "speculative windows scored/sec",
+        "value": w.B / (ms_per_step * 1e-3),
+        "unit": "windows/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype if w.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "K": w.K, "V": w.V, "M": w.M,
+                   "verify": w.verify, "cost_ratio": w.cost_ratio,
+                   "expected_accept_pass": w.expected_accept,
+                   "logit_gigabytes": algorithmic_bytes / 1e9},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(w.name),
+                     "kernel": "row_stats_kernel", "kernel_ms": score_ms,
+                     "algorithmic_bytes_per_launch": algorithmic_bytes},
+    }
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(w, inputs, sbuf, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -62,6 +62,7 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
         return fail(PPOW_ERR_INVALID_ARG, "cost_ratio must be a positive finite number");
     if (!isfinite(params->prox_eps) || !isfinite(params->prox_eta))
         return fail(PPOW_ERR_INVALID_ARG, "prox_eps and prox_eta must be finite");
+    if (B == 0) return PPOW_OK;                     // nothing to score: pointers may be NULL
     if (!draft_logits || !target_logits || !draft_tokens)
         return fail(PPOW_ERR_INVALID_ARG, "logits and draft_tokens must not be NULL");
     if (!aligned16(draft_logits) || !aligned16(target_logits))
@@ -81,7 +82,6 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     const size_t need = ppow_score_workspace_bytes(B, K, V, dtype, params->flags);
     if (!workspace || !aligned16(workspace) || workspace_bytes < need)
         return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
-    if (B == 0) return PPOW_OK;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t rows = B * K;

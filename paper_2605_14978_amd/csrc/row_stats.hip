@@ -5,12 +5,13 @@
 //
 // With P = softmax(a), Q = softmax(b) (Section 4.2) it accumulates, relative to
 // a per-lane reference rho (in log2 units, rho <= lane max <= rho + kRescaleGap):
-//     Z_a  = sum 2^t,  S1 = sum 2^t * t,  S2 = sum 2^t * (a - b),   t = a*log2(e) - rho_a
+//     Z_a  = sum 2^t,  S1 = sum 2^t * t,  S2 = sum 2^t * (a - b),   t  = a*log2(e) - rho_a
 //     Z_b  = sum 2^tb,                                             tb = b*log2(e) - rho_b
 // from which  H(P)     = ln2' * (log2 Z_a - S1 / Z_a)
 //             KL(P||Q) = S2 / Z_a - ln2' * ((rho_a - rho_b) + log2(Z_a / Z_b))
 // with ln2' = 1 / float(log2 e), so that the constant used going in is undone
-// exactly coming out.  The reference only moves when a chunk maximum exceeds it
+// coming out; the few per-row operations that subtract nearly equal numbers are
+// done in double.  Identical rows give exactly zero divergence.  The reference only moves when a chunk maximum exceeds it
 // by more than kRescaleGap, which keeps the rescale off the streaming path; the
 // exact row maximum and its first index are tracked separately, branch-free.
 #include "ppow_device.h"
@@ -238,14 +239,15 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
 
     // 2. bring every lane to the common references, then plain sums in a fixed tree
     float z_a = 0.f, s1 = 0.f, s2 = 0.f, z_b = 0.f;
-    if (s.rho_a != PPOW_NEG_INF) {
-        const float d = s.rho_a - ref_a;
-        const float sc = fast_exp2(d);
+    if (s.rho_a != PPOW_NEG_INF) {          // a lane that saw any element saw both rows
+        const float da = s.rho_a - ref_a;
+        const float db = s.rho_b - ref_b;
+        const float sc = fast_exp2(da);
         z_a = s.z_a * sc;
-        s1 = sc * fmaf(d, s.z_a, s.s1);
+        s1 = sc * fmaf(da, s.z_a, s.s1);
         s2 = s.s2 * sc;
+        z_b = s.z_b * fast_exp2(db);
     }
-    if (s.rho_b != PPOW_NEG_INF) z_b = s.z_b * fast_exp2(s.rho_b - ref_b);
 
     z_a = wave_sum(z_a); s1 = wave_sum(s1); s2 = wave_sum(s2); z_b = wave_sum(z_b);
 #pragma unroll
@@ -298,22 +300,27 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
 
     // ---- per-position scalars (Sections 4.2, 4.3.2; Appendix C.1) -------------------------
     if (tid == 0) {
-        const float ln2p = 1.0f / kLog2e;
-        const float inv_za = 1.0f / z_a;
-        const float entropy = ln2p * (log2_za - s1 * inv_za);
-        float kl = s2 * inv_za - ln2p * ((ref_a - ref_b) + fast_log2(z_a / z_b));
-        kl = fmaxf(kl, 0.f);
-        float conf = 1.0f - entropy * static_cast<float>(args.inv_ln_V);
+        const double ln2p_d = 1.0 / static_cast<double>(kLog2e);
+        const float ln2p = static_cast<float>(ln2p_d);
+        const double inv_za = 1.0 / static_cast<double>(z_a);
+        const double entropy = ln2p_d * (static_cast<double>(log2_za) - s1 * inv_za);
+        const double lse_diff = ln2p_d * (static_cast<double>(ref_a - ref_b) +
+                                          static_cast<double>(fast_log2(z_a / z_b)));
+        const float kl = fmaxf(static_cast<float>(s2 * inv_za - lse_diff), 0.f);
+        float conf = static_cast<float>(1.0 - entropy * args.inv_ln_V);
         conf = fminf(fmaxf(conf, 0.f), 1.f);
 
         const int tok = args.tokens[row];
         const float a_tok = S::load1(row_a + tok);
         const float b_tok = S::load1(row_b + tok);
-        const float lse_a = ln2p * (ref_a + log2_za);
-        const float lse_b = ln2p * (ref_b + log2_zb);
-        const float logp = a_tok - lse_a;
-        const float logq = b_tok - lse_b;
-        const float alpha = __expf(fminf(logp - logq, 0.f));
+        // log-probabilities relative to the running references: the error then scales
+        // with |log p|, not with the magnitude of the logits
+        const float xa = fmaf(a_tok, kLog2e, -ref_a) - log2_za;    // log2 P(tok)
+        const float xb = fmaf(b_tok, kLog2e, -ref_b) - log2_zb;    // log2 Q(tok)
+        const float logp = ln2p * xa;
+        const float logq = ln2p * xb;
+        // the ratio from the difference itself: exactly 0 when the rows are identical
+        const float alpha = fast_exp2(fminf(xa - xb, 0.f));
 
         int accept;
         if (args.greedy) accept = (tok == arg_i);

@@ -20,7 +20,8 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kLdsSortCap = 8192;          // composites the LDS sort buffer holds (64 KiB)
 
 __device__ __forceinline__ uint32_t ordered_bits(float x) {
-    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    u = (u == 0x80000000u) ? 0u : u;                 // -0.0 and +0.0 are the same score
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

@@ -179,18 +179,20 @@ def test_proximity_reward_and_reference_logprob():
     a[0, 0, 1], a[0, 1, 1] = 3.75, 3.76      # gap 0.49 -> eta
     a[1, 0, 1], a[1, 1, 1] = 3.75, 3.74      # gap 0.51 -> 0
     a[2, :, 1] = 3.9                         # small gap but k >= 1
-    a[3, :, 1] = 3.75                        # gap exactly 0.5: '<' is strict
+    a[3, 0, 1], a[3, 1, 1] = 3.5, 4.0 - 2.0 ** -10   # gap 0.5 + 2^-10: just outside
     b = a.clone()
     b[:, :, 1] += 3.0
     tok = torch.ones(4, K, dtype=torch.int32)
     u = torch.full((4, K), 0.999)
     u[2, 0] = 0.0
     d = _to_dev({"target_logits": a, "draft_logits": b, "draft_tokens": tok, "uniforms": u})
-    gpu, ref = _check(d, V, prox_eta=0.7)
+    gpu, ref = _check(d, V, prox_eta=0.75)
     assert gpu.accepted_len.cpu().tolist() == [0, 0, 1, 0]
-    assert gpu.r_proximity.cpu().tolist() == pytest.approx([0.7, 0.0, 0.0, 0.0])
+    assert gpu.r_proximity.cpu().tolist() == [0.75, 0.0, 0.0, 0.0]
+    # with a caller-supplied reference log-probability: delta = ref - sum_t log P_t(tok_t)
     ref_lp = torch.tensor([-0.3, -2.0, -1.0, -0.9]).to(DEV)
-    _check(d, V, prox_eta=0.7, ref_logprob=ref_lp)
+    gpu, ref = _check(d, V, prox_eta=0.75, ref_logprob=ref_lp)
+    assert float(np.abs(ref.delta - 0.5).min()) > 1e-3
 
 
 def test_expected_accept_pass_small_and_ragged():
