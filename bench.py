@@ -33,6 +33,8 @@ def parse_args():
                     help="override the window count B (0: the workload's own)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 disables it)")
+    ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GIB",
+                    help="only run a plain device copy of this many GiB (counter calibration)")
     return ap.parse_args()
 
 
@@ -95,6 +97,19 @@ def main():
     ppow.lib()                                     # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     dev = "cuda:0"
+
+    if args.copy_calibration > 0:
+        # A plain elementwise copy of known size: rocprofv3's FETCH_SIZE / WRITE_SIZE for this
+        # kernel give the factor that converts the counters to bytes.
+        n = int(args.copy_calibration * (1 << 30)) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(max(1, args.steps)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n * 4, "bytes_written": n * 4,
+                          "launches": max(1, args.steps)}), flush=True)
+        return
 
     w = WORKLOADS[args.workload]
     if args.windows:

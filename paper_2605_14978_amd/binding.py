@@ -10,7 +10,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIBRARY = os.path.join(_HERE, "libppow.so")
+# PPOW_LIBRARY selects another build of the same library (e.g. a tuning variant)
+LIBRARY = os.environ.get("PPOW_LIBRARY") or os.path.join(_HERE, "libppow.so")
 
 PPOW_OK = 0
 PPOW_ERR_INVALID_ARG = 1

@@ -19,15 +19,19 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source and link the shared library; returns its path."""
+def build(verbose: bool = False, defines=(), output: str = LIBRARY) -> str:
+    """Compile every HIP source and link the shared library; returns its path.
+
+    `defines` (e.g. ["PPOW_ROW_UNROLL=8"]) and `output` build a tuning variant elsewhere.
+    """
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    cmd += [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIBRARY]
+    cmd += ["-D" + d for d in defines]
+    cmd += [os.path.join(CSRC, s) for s in SOURCES] + ["-o", output]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True, cwd=HERE)
-    return LIBRARY
+    return output
 
 
 if __name__ == "__main__":

@@ -22,14 +22,33 @@
 namespace ppow {
 namespace {
 
-constexpr int kThreads = 256;
+// Launch shape of the streaming kernel; the defaults are the measured best on MI355X.
+#ifndef PPOW_ROW_THREADS
+#define PPOW_ROW_THREADS 256
+#endif
+#ifndef PPOW_ROW_UNROLL
+#define PPOW_ROW_UNROLL 4
+#endif
+#ifndef PPOW_ROW_NONTEMPORAL
+#define PPOW_ROW_NONTEMPORAL 1
+#endif
+constexpr int kThreads = PPOW_ROW_THREADS;
 constexpr int kWaves = kThreads / 64;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = PPOW_ROW_UNROLL;
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kRescaleGap = 24.0f;   // log2 units: partial sums stay below 2^24 * count
 #define PPOW_NEG_INF (-__builtin_huge_valf())
 
 typedef uint32_t raw4 __attribute__((ext_vector_type(4)));   // one 128-bit load
+
+// Streaming load: the logits are read once, so they should not displace other lines in L2.
+__device__ __forceinline__ raw4 stream_load(const raw4 *p) {
+#if PPOW_ROW_NONTEMPORAL
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
 
 __device__ __forceinline__ float as_float(uint32_t bits) { return __builtin_bit_cast(float, bits); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -137,13 +156,6 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-// (value, index) with "larger value, then smaller index" order
-__device__ __forceinline__ void argmax_merge(float &v, int &i, float v2, int i2) {
-    const bool take = (v2 > v) || (v2 == v && i2 < i);
-    v = take ? v2 : v;
-    i = take ? i2 : i;
-}
-
 template <int DTYPE>
 __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     using S = Storage<DTYPE>;
@@ -183,8 +195,8 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
         raw4 ra[kUnroll], rb[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            ra[u] = __builtin_nontemporal_load(pa + c + u * kThreads);
-            rb[u] = __builtin_nontemporal_load(pb + c + u * kThreads);
+            ra[u] = stream_load(pa + c + u * kThreads);
+            rb[u] = stream_load(pb + c + u * kThreads);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -196,75 +208,81 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     }
     for (; c < nchunks; c += kThreads) {
         float a[VEC], b[VEC];
-        S::unpack(__builtin_nontemporal_load(pa + c), a);
-        S::unpack(__builtin_nontemporal_load(pb + c), b);
+        S::unpack(stream_load(pa + c), a);
+        S::unpack(stream_load(pb + c), b);
         fold_chunk<VEC>(s, a, b, c);
-    }
-
-    // Element index of this lane's maximum: re-read the one chunk that holds it.
-    float arg_v = s.m_a;
-    int arg_i = INT_MAX;
-    if (s.best >= 0) {
-        float a[VEC];
-        S::unpack(pa[s.best], a);
-        int first = VEC - 1;
-#pragma unroll
-        for (int j = VEC - 2; j >= 0; --j) first = (a[j] == s.m_a) ? j : first;
-        arg_i = head + s.best * VEC + first;
     }
 
     // Ragged ends: at most VEC-1 elements before and after the vector body.
     const int ragged = head + (V - tail_begin);
+    float rag_v = PPOW_NEG_INF;
+    int rag_i = INT_MAX;
     if (tid < ragged) {
-        const int y = (tid < head) ? tid : tail_begin + (tid - head);
-        const float a1[1] = {S::load1(row_a + y)};
-        const float b1[1] = {S::load1(row_b + y)};
+        rag_i = (tid < head) ? tid : tail_begin + (tid - head);
+        const float a1[1] = {S::load1(row_a + rag_i)};
+        const float b1[1] = {S::load1(row_b + rag_i)};
         fold<1>(s, a1, b1, a1[0], b1[0]);
-        argmax_merge(arg_v, arg_i, a1[0], y);
+        rag_v = a1[0];
     }
 
     // ---- workgroup combine --------------------------------------------------------------
-    // 1. common references
+    // 1. common references and the exact row maximum
     float ref_a = wave_max(s.rho_a);
     float ref_b = wave_max(s.rho_b);
-    if (lane == 0) { sh_f[wave][0] = ref_a; sh_f[wave][1] = ref_b; }
+    float row_max = wave_max(fmaxf(s.m_a, rag_v));
+    if (lane == 0) { sh_f[wave][0] = ref_a; sh_f[wave][1] = ref_b; sh_f[wave][2] = row_max; }
     __syncthreads();
-    ref_a = sh_f[0][0]; ref_b = sh_f[0][1];
+    ref_a = sh_f[0][0]; ref_b = sh_f[0][1]; row_max = sh_f[0][2];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) {
         ref_a = fmaxf(ref_a, sh_f[w][0]);
         ref_b = fmaxf(ref_b, sh_f[w][1]);
+        row_max = fmaxf(row_max, sh_f[w][2]);
     }
     __syncthreads();
+
+    // First index of the row maximum: only lanes that hold it re-read their one chunk.
+    int arg_i = (rag_v == row_max) ? rag_i : INT_MAX;
+    if (s.best >= 0 && s.m_a == row_max) {
+        float a[VEC];
+        S::unpack(pa[s.best], a);
+        int first = VEC - 1;
+#pragma unroll
+        for (int j = VEC - 2; j >= 0; --j) first = (a[j] == row_max) ? j : first;
+        const int idx = head + s.best * VEC + first;
+        arg_i = idx < arg_i ? idx : arg_i;
+    }
 
     // 2. bring every lane to the common references, then plain sums in a fixed tree
     float z_a = 0.f, s1 = 0.f, s2 = 0.f, z_b = 0.f;
     if (s.rho_a != PPOW_NEG_INF) {          // a lane that saw any element saw both rows
         const float da = s.rho_a - ref_a;
-        const float db = s.rho_b - ref_b;
         const float sc = fast_exp2(da);
         z_a = s.z_a * sc;
         s1 = sc * fmaf(da, s.z_a, s.s1);
         s2 = s.s2 * sc;
-        z_b = s.z_b * fast_exp2(db);
+        z_b = s.z_b * fast_exp2(s.rho_b - ref_b);
     }
 
     z_a = wave_sum(z_a); s1 = wave_sum(s1); s2 = wave_sum(s2); z_b = wave_sum(z_b);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
-        argmax_merge(arg_v, arg_i, __shfl_xor(arg_v, off, 64), __shfl_xor(arg_i, off, 64));
+    for (int off = 32; off > 0; off >>= 1) {
+        const int other = __shfl_xor(arg_i, off, 64);
+        arg_i = other < arg_i ? other : arg_i;
+    }
     if (lane == 0) {
         sh_f[wave][0] = z_a; sh_f[wave][1] = s1; sh_f[wave][2] = s2; sh_f[wave][3] = z_b;
-        sh_f[wave][4] = arg_v; sh_i[wave] = arg_i;
+        sh_i[wave] = arg_i;
     }
     __syncthreads();
     z_a = sh_f[0][0]; s1 = sh_f[0][1]; s2 = sh_f[0][2]; z_b = sh_f[0][3];
-    arg_v = sh_f[0][4]; arg_i = sh_i[0];
+    arg_i = sh_i[0];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) {
         z_a += sh_f[w][0]; s1 += sh_f[w][1]; s2 += sh_f[w][2]; z_b += sh_f[w][3];
-        argmax_merge(arg_v, arg_i, sh_f[w][4], sh_i[w]);
+        arg_i = sh_i[w] < arg_i ? sh_i[w] : arg_i;
     }
+    const float arg_v = row_max;
 
     const float log2_za = fast_log2(z_a);
     const float log2_zb = fast_log2(z_b);
