@@ -137,7 +137,7 @@ class ScoreBuffers:
         for name in ("accepted_len", "r_speedup", "r_proximity", "adaw_score") + OPTIONAL_OUTPUTS:
             t = getattr(self, name)
             setattr(view, name, None if t is None else t[w0:w1])
-        view.workspace = self.workspace
+        view.workspace = self.workspace     # shared: calls on one stream run one after another
         return view
 
     def as_struct(self):

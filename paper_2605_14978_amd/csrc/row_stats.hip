@@ -41,13 +41,14 @@ constexpr float kRescaleGap = 24.0f;   // log2 units: partial sums stay below 2^
 
 typedef uint32_t raw4 __attribute__((ext_vector_type(4)));   // one 128-bit load
 
-// Streaming load: the logits are read once, so they should not displace other lines in L2.
-__device__ __forceinline__ raw4 stream_load(const raw4 *p) {
+// Streaming load: logits that will not be read again should not displace other lines in
+// cache (STREAM); a row that the second pass re-reads is loaded normally the first time.
+template <bool STREAM>
+__device__ __forceinline__ raw4 load_chunk(const raw4 *p) {
 #if PPOW_ROW_NONTEMPORAL
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
+    if (STREAM) return __builtin_nontemporal_load(p);
 #endif
+    return *p;
 }
 
 __device__ __forceinline__ float as_float(uint32_t bits) { return __builtin_bit_cast(float, bits); }
@@ -156,7 +157,7 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-template <int DTYPE>
+template <int DTYPE, bool SECOND>
 __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     using S = Storage<DTYPE>;
     using elem = typename S::elem;
@@ -195,8 +196,8 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
         raw4 ra[kUnroll], rb[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            ra[u] = stream_load(pa + c + u * kThreads);
-            rb[u] = stream_load(pb + c + u * kThreads);
+            ra[u] = load_chunk<!SECOND>(pa + c + u * kThreads);
+            rb[u] = load_chunk<!SECOND>(pb + c + u * kThreads);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -208,8 +209,8 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     }
     for (; c < nchunks; c += kThreads) {
         float a[VEC], b[VEC];
-        S::unpack(stream_load(pa + c), a);
-        S::unpack(stream_load(pb + c), b);
+        S::unpack(load_chunk<!SECOND>(pa + c), a);
+        S::unpack(load_chunk<!SECOND>(pb + c), b);
         fold_chunk<VEC>(s, a, b, c);
     }
 
@@ -289,14 +290,35 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
 
     // ---- optional second pass: sum_y min(P(y), Q(y))  (Appendix B.1) ----------------------
     float expected = 0.f;
-    if (args.second_pass) {
+    if (SECOND) {
+        // The row is walked backwards: its end was read last and is the most likely part to
+        // still sit in the L2 / memory-side cache.
         const float lam_a = ref_a + log2_za;      // log2-domain log-sum-exp
         const float lam_b = ref_b + log2_zb;
         float acc = 0.f;
-        for (int cc = tid; cc < nchunks; cc += kThreads) {
+        int cc = nchunks - 1 - tid;
+        for (; cc - (kUnroll - 1) * kThreads >= 0; cc -= kUnroll * kThreads) {
+            raw4 ra[kUnroll], rb[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                ra[u] = load_chunk<true>(pa + cc - u * kThreads);
+                rb[u] = load_chunk<true>(pb + cc - u * kThreads);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float a[VEC], b[VEC];
+                S::unpack(ra[u], a);
+                S::unpack(rb[u], b);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j)
+                    acc += fminf(fast_exp2(fmaf(a[j], kLog2e, -lam_a)),
+                                 fast_exp2(fmaf(b[j], kLog2e, -lam_b)));
+            }
+        }
+        for (; cc >= 0; cc -= kThreads) {
             float a[VEC], b[VEC];
-            S::unpack(pa[cc], a);
-            S::unpack(pb[cc], b);
+            S::unpack(load_chunk<true>(pa + cc), a);
+            S::unpack(load_chunk<true>(pb + cc), b);
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
                 acc += fminf(fast_exp2(fmaf(a[j], kLog2e, -lam_a)),
@@ -362,13 +384,33 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
 
 }  // namespace
 
+// Dynamic LDS requested only to cap how many two-pass workgroups share a CU, so that the rows
+// in flight fit the memory-side cache when they are read the second time.
+#ifndef PPOW_PASS2_LDS_BYTES
+#define PPOW_PASS2_LDS_BYTES 0
+#endif
+
 hipError_t launch_row_stats(const RowArgs &args, int64_t rows, int32_t dtype, hipStream_t stream) {
     if (rows == 0) return hipSuccess;
     const dim3 grid(static_cast<unsigned>(rows)), block(kThreads);
-    if (dtype == PPOW_BF16)
-        hipLaunchKernelGGL(row_stats_kernel<PPOW_BF16>, grid, block, 0, stream, args);
-    else
-        hipLaunchKernelGGL(row_stats_kernel<PPOW_F32>, grid, block, 0, stream, args);
+    if (args.second_pass) {
+        const size_t lds = PPOW_PASS2_LDS_BYTES;
+        if (dtype == PPOW_BF16) {
+            if (lds > 65536)
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(row_stats_kernel<PPOW_BF16, true>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            hipLaunchKernelGGL((row_stats_kernel<PPOW_BF16, true>), grid, block, lds, stream, args);
+        } else {
+            if (lds > 65536)
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(row_stats_kernel<PPOW_F32, true>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            hipLaunchKernelGGL((row_stats_kernel<PPOW_F32, true>), grid, block, lds, stream, args);
+        }
+    } else if (dtype == PPOW_BF16) {
+        hipLaunchKernelGGL((row_stats_kernel<PPOW_BF16, false>), grid, block, 0, stream, args);
+    } else {
+        hipLaunchKernelGGL((row_stats_kernel<PPOW_F32, false>), grid, block, 0, stream, args);
+    }
     return hipGetLastError();
 }
 
