@@ -11,6 +11,7 @@ bounded sample of the same inputs.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -33,6 +34,8 @@ def parse_args():
                     help="override the window count B (0: the workload's own)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="CPU time budget of the oracle baseline (0 disables it)")
+    ap.add_argument("--expected-accept", action="store_true",
+                    help="force the expected-acceptance second pass on for this workload")
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GIB",
                     help="only run a plain device copy of this many GiB (counter calibration)")
     return ap.parse_args()
@@ -114,6 +117,8 @@ def main():
     w = WORKLOADS[args.workload]
     if args.windows:
         w = w.scaled(args.windows)
+    if args.expected_accept:
+        w = dataclasses.replace(w, expected_accept=True)
     print(f"# {describe(w)}", file=sys.stderr, flush=True)
 
     # A workload of several chunks streams them through the scoring call one after another
@@ -193,7 +198,8 @@ def main():
                    "logit_gigabytes_per_step": algorithmic_bytes * w.chunks / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(w.name),
-                     "kernel": "row_stats_kernel", "kernel_ms": score_ms,
+                     "kernel": "row_%s_kernel" % ("cluster" if ppow.last_row_kernel() == "cluster" else "stats"),
+                     "kernel_ms": score_ms,
                      "algorithmic_bytes_per_launch": algorithmic_bytes},
     }
     if args.cpu_seconds > 0:

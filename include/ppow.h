@@ -46,8 +46,14 @@ typedef enum { PPOW_VERIFY_REJECTION = 0, PPOW_VERIFY_GREEDY = 1 } ppow_verify;
 enum {
     /* also compute sum_y min(P_t(y), Q_t(y)), the expected acceptance probability
      * of Appendix B.1; it needs normalised probabilities, hence a second pass over
-     * each row pair (issued right after the first so that it is served by cache) */
-    PPOW_FLAG_EXPECTED_ACCEPT = 1u
+     * each row pair, served from LDS (a cluster of workgroups shares a row pair)
+     * where the device allows a cooperative launch, from memory otherwise */
+    PPOW_FLAG_EXPECTED_ACCEPT = 1u,
+    /* also compute the forward values of the policy-loss terms from the same pass:
+     * KL(Q_t || P_t), the target-anchored regulariser of Section 4.1 / Appendix A.2,
+     * and the alignment metric exp(d) - d - 1, d = log P_t(tok) - log Q_t(tok), of
+     * Appendix E; one more multiply-add per logit pair */
+    PPOW_FLAG_POLICY_TERMS = 2u
 };
 
 #define PPOW_MAX_K 64          /* drafted positions per window (one wavefront) */
@@ -58,6 +64,9 @@ typedef struct {
     float prox_eta;    /* eta: proximity reward scale, Table 5 default 1.0              */
     int32_t verify;    /* ppow_verify                                                   */
     uint32_t flags;    /* PPOW_FLAG_*                                                   */
+    int32_t rollout_group; /* G: windows per rollout group for `advantage` (Table 5: 8);
+                              0 when the advantage output is not used; must divide B    */
+    float adv_delta;   /* small positive constant in the advantage normalisation        */
 } ppow_params;
 
 /* Device output arrays.  The first four are required; the rest may be NULL. */
@@ -73,10 +82,21 @@ typedef struct {
     float *expected_accept;  /* [B*K] sum_y min(P_t, Q_t); needs PPOW_FLAG_EXPECTED_ACCEPT    */
     float *logp_target_tok;  /* [B*K] log P_t(drafted token)                                  */
     float *logp_draft_tok;   /* [B*K] log Q_t(drafted token)                                  */
+    float *reverse_kl;       /* [B*K] KL(Q_t || P_t); needs PPOW_FLAG_POLICY_TERMS            */
+    float *alignment;        /* [B*K] exp(d) - d - 1 (Appendix E); needs PPOW_FLAG_POLICY_TERMS */
+    float *reverse_kl_mean;  /* [B]   mean over the window's K positions; same flag           */
+    float *alignment_mean;   /* [B]   mean over the window's K positions; same flag           */
+    float *advantage;        /* [B]   group-relative advantage (R_i - mean)/(std + delta) of
+                                      R_i = r_speedup + r_proximity over groups of
+                                      rollout_group consecutive windows (Section 4.1);
+                                      population standard deviation; needs rollout_group >= 1 */
 } ppow_outputs;
 
 /* Bytes of device workspace ppow_score_windows needs for these sizes (0 on
- * invalid sizes).  The workspace must be 16-byte aligned. */
+ * invalid sizes).  The workspace must be 16-byte aligned.  After the stream has
+ * drained, the first 32-bit word of the workspace is 0 unless the bounded wait
+ * inside the cluster variant of the row kernel expired, which is not expected to
+ * happen; the outputs of that call are then invalid. */
 size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype, uint32_t flags);
 
 /*
@@ -130,6 +150,11 @@ int ppow_select_windows(const float *adaw_score, int64_t B, int32_t M,
 
 /* Message of the calling thread's most recent failed call (static storage). */
 const char *ppow_last_error(void);
+
+/* Which streaming kernel the calling thread's most recent ppow_score_windows call
+ * launched: "row" (one workgroup per row pair), "cluster" (a cluster of workgroups
+ * per row pair, second pass from LDS) or "none".  Static storage. */
+const char *ppow_last_row_kernel(void);
 
 /* Library version, "major.minor.patch". */
 const char *ppow_version(void);

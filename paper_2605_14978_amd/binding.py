@@ -24,6 +24,7 @@ PPOW_BF16 = 1
 PPOW_VERIFY_REJECTION = 0
 PPOW_VERIFY_GREEDY = 1
 PPOW_FLAG_EXPECTED_ACCEPT = 1
+PPOW_FLAG_POLICY_TERMS = 2
 PPOW_MAX_K = 64
 
 _f32p = ctypes.POINTER(ctypes.c_float)
@@ -33,7 +34,8 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 class PpowParams(ctypes.Structure):
     _fields_ = [("cost_ratio", ctypes.c_float), ("prox_eps", ctypes.c_float),
                 ("prox_eta", ctypes.c_float), ("verify", ctypes.c_int32),
-                ("flags", ctypes.c_uint32)]
+                ("flags", ctypes.c_uint32), ("rollout_group", ctypes.c_int32),
+                ("adv_delta", ctypes.c_float)]
 
 
 class PpowOutputs(ctypes.Structure):
@@ -42,7 +44,9 @@ class PpowOutputs(ctypes.Structure):
                 ("delta", ctypes.c_void_p), ("kl", ctypes.c_void_p),
                 ("confidence", ctypes.c_void_p), ("accept_prob", ctypes.c_void_p),
                 ("expected_accept", ctypes.c_void_p), ("logp_target_tok", ctypes.c_void_p),
-                ("logp_draft_tok", ctypes.c_void_p)]
+                ("logp_draft_tok", ctypes.c_void_p), ("reverse_kl", ctypes.c_void_p),
+                ("alignment", ctypes.c_void_p), ("reverse_kl_mean", ctypes.c_void_p),
+                ("alignment_mean", ctypes.c_void_p), ("advantage", ctypes.c_void_p)]
 
 
 class PpowError(RuntimeError):
@@ -75,10 +79,17 @@ def lib():
         L.ppow_select_windows.restype = ctypes.c_int
         L.ppow_last_error.argtypes = []
         L.ppow_last_error.restype = ctypes.c_char_p
+        L.ppow_last_row_kernel.argtypes = []
+        L.ppow_last_row_kernel.restype = ctypes.c_char_p
         L.ppow_version.argtypes = []
         L.ppow_version.restype = ctypes.c_char_p
         _lib = L
     return _lib
+
+
+def last_row_kernel():
+    """Name of the streaming kernel the last scoring call of this thread launched."""
+    return lib().ppow_last_row_kernel().decode()
 
 
 def _check(status):
@@ -104,7 +115,9 @@ def _dtype_code(t):
 
 
 OPTIONAL_OUTPUTS = ("delta", "kl", "confidence", "accept_prob", "expected_accept",
-                    "logp_target_tok", "logp_draft_tok")
+                    "logp_target_tok", "logp_draft_tok", "reverse_kl", "alignment",
+                    "reverse_kl_mean", "alignment_mean", "advantage")
+PER_WINDOW_OPTIONAL = ("delta", "reverse_kl_mean", "alignment_mean", "advantage")
 
 
 class ScoreBuffers:
@@ -120,9 +133,9 @@ class ScoreBuffers:
         for name in OPTIONAL_OUTPUTS:
             t = None
             if name in optional:
-                n = B if name == "delta" else B * K
+                n = B if name in PER_WINDOW_OPTIONAL else B * K
                 t = torch.empty(n, dtype=torch.float32, device=dev)
-                if name != "delta":
+                if name not in PER_WINDOW_OPTIONAL:
                     t = t.view(B, K)
             setattr(self, name, t)
         nbytes = lib().ppow_score_workspace_bytes(B, K, V, dtype_code, flags)
@@ -140,6 +153,10 @@ class ScoreBuffers:
         view.workspace = self.workspace     # shared: calls on one stream run one after another
         return view
 
+    def status(self):
+        """First word of the workspace: 0 unless the cluster kernel's bounded wait expired."""
+        return int(self.workspace[:4].view(torch.int32).item())
+
     def as_struct(self):
         o = PpowOutputs()
         for name, _ in PpowOutputs._fields_:
@@ -150,7 +167,8 @@ class ScoreBuffers:
 
 def ppow_score_windows(draft_logits, target_logits, draft_tokens, uniforms=None, ref_logprob=None,
                        *, cost_ratio, prox_eps=0.5, prox_eta=1.0, verify=PPOW_VERIFY_REJECTION,
-                       flags=0, optional=(), buffers=None, stream=None):
+                       flags=0, rollout_group=0, adv_delta=1e-6, optional=(), buffers=None,
+                       stream=None):
     """Score B windows on the GPU; returns the ScoreBuffers holding the device outputs.
 
     Tensors are CUDA tensors: logits [B, K, V] contiguous float32 / bfloat16,
@@ -175,7 +193,8 @@ def ppow_score_windows(draft_logits, target_logits, draft_tokens, uniforms=None,
     code = _dtype_code(target_logits)
     if buffers is None:
         buffers = ScoreBuffers(B, K, V, code, target_logits.device, optional, flags)
-    params = PpowParams(float(cost_ratio), float(prox_eps), float(prox_eta), int(verify), int(flags))
+    params = PpowParams(float(cost_ratio), float(prox_eps), float(prox_eta), int(verify), int(flags),
+                        int(rollout_group), float(adv_delta))
     outs = buffers.as_struct()
     _check(lib().ppow_score_windows(
         _ptr(draft_logits), _ptr(target_logits), _ptr(draft_tokens), _ptr(uniforms),

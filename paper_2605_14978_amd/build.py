@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIBRARY = os.path.join(HERE, "libppow.so")
-SOURCES = ["api.hip", "row_stats.hip", "window_epilogue.hip", "select.hip"]
+SOURCES = ["api.hip", "row_stats.hip", "row_cluster.hip", "window_epilogue.hip", "select.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -10,6 +10,7 @@
 namespace {
 
 thread_local char g_error[256] = "";
+thread_local const char *g_row_kernel = "none";
 
 int fail(ppow_status code, const char *fmt, ...) {
     va_list ap;
@@ -34,13 +35,16 @@ extern "C" {
 
 const char *ppow_last_error(void) { return g_error; }
 
-const char *ppow_version(void) { return "0.1.0"; }
+const char *ppow_version(void) { return "0.2.0"; }
+
+const char *ppow_last_row_kernel(void) { return g_row_kernel; }
 
 size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype, uint32_t flags) {
     (void)flags;
     if (!sizes_ok(B, K, V, dtype)) return 0;
-    const size_t bytes = static_cast<size_t>(B) * static_cast<size_t>(K) * sizeof(ppow::RowRecord);
-    return bytes < 256 ? 256 : bytes;
+    // [scratch of the cluster kernel][one record per (window, position)]
+    return ppow::kClusterScratchBytes +
+           static_cast<size_t>(B) * static_cast<size_t>(K) * sizeof(ppow::RowRecord);
 }
 
 int ppow_score_windows(const void *draft_logits, const void *target_logits,
@@ -56,7 +60,7 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
                     (long long)B, K, (long long)V, dtype, PPOW_MAX_K);
     if (params->verify != PPOW_VERIFY_REJECTION && params->verify != PPOW_VERIFY_GREEDY)
         return fail(PPOW_ERR_INVALID_ARG, "unknown verify mode %d", params->verify);
-    if (params->flags & ~static_cast<uint32_t>(PPOW_FLAG_EXPECTED_ACCEPT))
+    if (params->flags & ~static_cast<uint32_t>(PPOW_FLAG_EXPECTED_ACCEPT | PPOW_FLAG_POLICY_TERMS))
         return fail(PPOW_ERR_INVALID_ARG, "unknown flag bits 0x%x", params->flags);
     if (!(params->cost_ratio > 0.f) || !isfinite(params->cost_ratio))
         return fail(PPOW_ERR_INVALID_ARG, "cost_ratio must be a positive finite number");
@@ -79,6 +83,19 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     if (second_pass && !out->expected_accept)
         return fail(PPOW_ERR_INVALID_ARG,
                     "PPOW_FLAG_EXPECTED_ACCEPT needs the expected_accept output");
+    const bool policy_terms = (params->flags & PPOW_FLAG_POLICY_TERMS) != 0;
+    if (!policy_terms && (out->reverse_kl || out->alignment || out->reverse_kl_mean ||
+                          out->alignment_mean))
+        return fail(PPOW_ERR_INVALID_ARG,
+                    "reverse_kl / alignment outputs need PPOW_FLAG_POLICY_TERMS");
+    if (out->advantage) {
+        if (params->rollout_group < 1 || B % params->rollout_group != 0)
+            return fail(PPOW_ERR_INVALID_ARG,
+                        "advantage needs rollout_group >= 1 dividing B (got %d, B=%lld)",
+                        params->rollout_group, (long long)B);
+        if (!(params->adv_delta >= 0.f) || !isfinite(params->adv_delta))
+            return fail(PPOW_ERR_INVALID_ARG, "adv_delta must be a finite number >= 0");
+    }
     const size_t need = ppow_score_workspace_bytes(B, K, V, dtype, params->flags);
     if (!workspace || !aligned16(workspace) || workspace_bytes < need)
         return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
@@ -91,7 +108,8 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     ra.draft = draft_logits;
     ra.tokens = draft_tokens;
     ra.uniforms = uniforms;
-    ra.records = static_cast<ppow::RowRecord *>(workspace);
+    ra.records = reinterpret_cast<ppow::RowRecord *>(static_cast<char *>(workspace) +
+                                                      ppow::kClusterScratchBytes);
     ra.kl = out->kl;
     ra.confidence = out->confidence;
     ra.accept_prob = out->accept_prob;
@@ -101,10 +119,25 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     ra.V = V;
     ra.inv_ln_V = 1.0 / log(static_cast<double>(V));
     ra.greedy = params->verify == PPOW_VERIFY_GREEDY;
+    ra.reverse_kl = out->reverse_kl;
+    ra.alignment = out->alignment;
     ra.second_pass = second_pass;
-    hipError_t err = ppow::launch_row_stats(ra, rows, dtype, stream);
-    if (err != hipSuccess)
-        return fail(PPOW_ERR_DEVICE, "row kernel launch failed: %s", hipGetErrorString(err));
+    ra.want_policy_terms = policy_terms;
+    hipError_t err = hipSuccess;
+    bool launched = false;
+    if (second_pass) {
+        // preferred: second pass from LDS; falls through when the device or sizes rule it out
+        err = ppow::launch_row_cluster(ra, rows, dtype, workspace, stream, &launched);
+        if (err != hipSuccess)
+            return fail(PPOW_ERR_DEVICE, "cluster row kernel launch failed: %s",
+                        hipGetErrorString(err));
+    }
+    g_row_kernel = launched ? "cluster" : "row";
+    if (!launched) {
+        err = ppow::launch_row_stats(ra, rows, dtype, stream);
+        if (err != hipSuccess)
+            return fail(PPOW_ERR_DEVICE, "row kernel launch failed: %s", hipGetErrorString(err));
+    }
 
     ppow::WindowArgs wa;
     wa.records = ra.records;
@@ -114,6 +147,9 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     wa.r_proximity = out->r_proximity;
     wa.adaw_score = out->adaw_score;
     wa.delta = out->delta;
+    wa.reverse_kl_mean = out->reverse_kl_mean;
+    wa.alignment_mean = out->alignment_mean;
+    wa.status_clear = launched ? nullptr : static_cast<uint32_t *>(workspace);
     wa.B = B;
     wa.K = K;
     wa.cost_ratio = params->cost_ratio;
@@ -122,6 +158,20 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     err = ppow::launch_window_epilogue(wa, stream);
     if (err != hipSuccess)
         return fail(PPOW_ERR_DEVICE, "window kernel launch failed: %s", hipGetErrorString(err));
+
+    if (out->advantage) {
+        ppow::AdvantageArgs aa;
+        aa.r_speedup = out->r_speedup;
+        aa.r_proximity = out->r_proximity;
+        aa.advantage = out->advantage;
+        aa.group = params->rollout_group;
+        aa.groups = B / params->rollout_group;
+        aa.delta_stab = params->adv_delta;
+        err = ppow::launch_group_advantage(aa, stream);
+        if (err != hipSuccess)
+            return fail(PPOW_ERR_DEVICE, "advantage kernel launch failed: %s",
+                        hipGetErrorString(err));
+    }
     return PPOW_OK;
 }
 

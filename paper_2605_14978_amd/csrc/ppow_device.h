@@ -15,7 +15,11 @@ struct RowRecord {
     float gap;           // max_y a_t[y] - a_t[tok_t]                 (Section 4.3.2, same-context reference)
     float logp_tok;      // log P_t(tok_t)
     int32_t accept;      // verification outcome of this position     (Appendix C.1)
+    float reverse_kl;    // KL(Q_t || P_t)                            (Section 4.1, Appendix A.2)
+    float alignment;     // exp(d) - d - 1, d = log P_t(tok) - log Q_t(tok)   (Appendix E)
+    float pad0, pad1;
 };
+static_assert(sizeof(RowRecord) == 32, "records are 32 bytes");
 
 struct RowArgs {
     const void *target;          // [rows, V]
@@ -29,10 +33,13 @@ struct RowArgs {
     float *expected_accept;
     float *logp_target_tok;
     float *logp_draft_tok;
+    float *reverse_kl;
+    float *alignment;
     int64_t V;
     double inv_ln_V;             // 1 / ln V
     int32_t greedy;              // 1: accept iff token == argmax target
     int32_t second_pass;         // 1: compute sum_y min(P, Q)
+    int32_t want_policy_terms;   // 1: compute KL(Q||P) and the alignment metric
 };
 
 struct WindowArgs {
@@ -43,13 +50,31 @@ struct WindowArgs {
     float *r_proximity;          // [B]
     float *adaw_score;           // [B]
     float *delta;                // [B] or nullptr
+    float *reverse_kl_mean;      // [B] or nullptr
+    float *alignment_mean;       // [B] or nullptr
+    uint32_t *status_clear;      // workspace status word to zero, or nullptr (cluster path owns it)
     int64_t B;
     int32_t K;
     float cost_ratio, prox_eps, prox_eta;
 };
 
+struct AdvantageArgs {
+    const float *r_speedup;      // [B]
+    const float *r_proximity;    // [B]
+    float *advantage;            // [B]
+    int64_t groups;              // B / group
+    int32_t group;               // rollout group size G
+    float delta_stab;            // small positive constant of the normalisation
+};
+
+// Scratch words of the cluster variant of the row kernel, kept in front of the records.
+constexpr size_t kClusterScratchBytes = 1u << 20;
+
 hipError_t launch_row_stats(const RowArgs &args, int64_t rows, int32_t dtype, hipStream_t stream);
+hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, void *scratch,
+                              hipStream_t stream, bool *launched);
 hipError_t launch_window_epilogue(const WindowArgs &args, hipStream_t stream);
+hipError_t launch_group_advantage(const AdvantageArgs &args, hipStream_t stream);
 
 size_t select_workspace_bytes(int64_t B, int32_t M);
 hipError_t launch_select(const float *score, int64_t B, int32_t M, int32_t *indices, float *scores,

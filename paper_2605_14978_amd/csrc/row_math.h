@@ -1,0 +1,290 @@
+// Device-side arithmetic shared by the two row kernels (one workgroup per row pair, and a
+// cluster of workgroups per row pair): storage unpacking, the per-lane online softmax state,
+// wave reductions and the per-position epilogue.
+//
+// With P = softmax(a), Q = softmax(b) (Section 4.2) a lane accumulates, relative to its own
+// references rho (log2 units; rho <= lane max <= rho + kRescaleGap):
+//     Z_a = sum 2^t,  S1 = sum 2^t * t,  S2 = sum 2^t * (a - b),    t  = a*log2(e) - rho_a
+//     Z_b = sum 2^tb,                    S2r = sum 2^tb * (b - a),  tb = b*log2(e) - rho_b
+// from which  H(P)     = ln2' * (log2 Z_a - S1 / Z_a)
+//             KL(P||Q) = S2  / Z_a - ln2' * ((rho_a - rho_b) + log2(Z_a / Z_b))
+//             KL(Q||P) = S2r / Z_b + ln2' * ((rho_a - rho_b) + log2(Z_a / Z_b))
+// with ln2' = 1 / float(log2 e), so that the constant used going in is undone coming out;
+// the few per-row operations that subtract nearly equal numbers are done in double.
+// Identical rows give exactly zero divergence.  A reference only moves when a chunk maximum
+// exceeds it by more than kRescaleGap, which keeps the rescale off the streaming path; the
+// exact row maximum and its first index are tracked separately, branch-free.
+#pragma once
+
+#include <limits.h>
+#include <math.h>
+
+#include "ppow_device.h"
+
+namespace ppow {
+
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kRescaleGap = 24.0f;   // log2 units: partial sums stay below 2^24 * count
+#define PPOW_NEG_INF (-__builtin_huge_valf())
+
+#ifndef PPOW_ROW_NONTEMPORAL
+#define PPOW_ROW_NONTEMPORAL 1
+#endif
+
+typedef uint32_t raw4 __attribute__((ext_vector_type(4)));   // one 128-bit load
+
+// Streaming load: logits that will not be read again should not displace other lines in
+// cache (STREAM); a row that a second pass re-reads from memory is loaded normally.
+template <bool STREAM>
+__device__ __forceinline__ raw4 load_chunk(const raw4 *p) {
+#if PPOW_ROW_NONTEMPORAL
+    if (STREAM) return __builtin_nontemporal_load(p);
+#endif
+    return *p;
+}
+
+__device__ __forceinline__ float as_float(uint32_t bits) { return __builtin_bit_cast(float, bits); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+template <int DTYPE>
+struct Storage;
+
+template <>
+struct Storage<PPOW_F32> {
+    using elem = float;
+    static constexpr int VEC = 4;
+    static __device__ __forceinline__ void unpack(const raw4 &r, float (&x)[VEC]) {
+        x[0] = as_float(r.x); x[1] = as_float(r.y); x[2] = as_float(r.z); x[3] = as_float(r.w);
+    }
+    static __device__ __forceinline__ float load1(const elem *p) { return *p; }
+};
+
+template <>
+struct Storage<PPOW_BF16> {
+    using elem = uint16_t;
+    static constexpr int VEC = 8;
+    // a bfloat16 is the upper half of a binary32; element 2i sits in the low half of word i
+    static __device__ __forceinline__ void unpack(const raw4 &r, float (&x)[VEC]) {
+        x[0] = as_float(r.x << 16); x[1] = as_float(r.x & 0xffff0000u);
+        x[2] = as_float(r.y << 16); x[3] = as_float(r.y & 0xffff0000u);
+        x[4] = as_float(r.z << 16); x[5] = as_float(r.z & 0xffff0000u);
+        x[6] = as_float(r.w << 16); x[7] = as_float(r.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ float load1(const elem *p) {
+        return as_float(static_cast<uint32_t>(*p) << 16);
+    }
+};
+
+struct LaneState {
+    float rho_a, z_a, s1, s2;   // target side
+    float rho_b, z_b, s2r;      // draft side (s2r only when the reverse divergence is wanted)
+    float m_a;                  // exact maximum of the target logits this lane has seen
+    int best;                   // body chunk in which m_a was first reached (-1: none yet)
+
+    __device__ __forceinline__ void reset() {
+        rho_a = PPOW_NEG_INF; z_a = 0.f; s1 = 0.f; s2 = 0.f;
+        rho_b = PPOW_NEG_INF; z_b = 0.f; s2r = 0.f;
+        m_a = PPOW_NEG_INF; best = -1;
+    }
+};
+
+__device__ __forceinline__ void rebase_target(LaneState &s, float new_rho) {
+    if (s.rho_a == PPOW_NEG_INF) {
+        s.z_a = 0.f; s.s1 = 0.f; s.s2 = 0.f;
+    } else {
+        const float d = s.rho_a - new_rho;
+        const float sc = fast_exp2(d);
+        s.s1 = sc * fmaf(d, s.z_a, s.s1);     // every t shifts by d
+        s.z_a *= sc;
+        s.s2 *= sc;
+    }
+    s.rho_a = new_rho;
+}
+
+__device__ __forceinline__ void rebase_draft(LaneState &s, float new_rho) {
+    const float sc = (s.rho_b == PPOW_NEG_INF) ? 0.f : fast_exp2(s.rho_b - new_rho);
+    s.z_b *= sc;
+    s.s2r *= sc;
+    s.rho_b = new_rho;
+}
+
+// Fold VEC element pairs into the running sums (no argmax bookkeeping).
+template <int VEC, bool REV>
+__device__ __forceinline__ void fold(LaneState &s, const float (&a)[VEC], const float (&b)[VEC],
+                                     float cma, float cmb) {
+    const float ta_max = fmaf(cma, kLog2e, -s.rho_a);
+    const float tb_max = fmaf(cmb, kLog2e, -s.rho_b);
+    if (fmaxf(ta_max, tb_max) > kRescaleGap) {      // rare: the reference lags too far behind
+        if (ta_max > kRescaleGap) rebase_target(s, cma * kLog2e);
+        if (tb_max > kRescaleGap) rebase_draft(s, cmb * kLog2e);
+    }
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+        const float t = fmaf(a[j], kLog2e, -s.rho_a);
+        const float e = fast_exp2(t);
+        const float d = a[j] - b[j];
+        s.z_a += e;
+        s.s1 = fmaf(e, t, s.s1);
+        s.s2 = fmaf(e, d, s.s2);
+        const float tb = fmaf(b[j], kLog2e, -s.rho_b);
+        const float eb = fast_exp2(tb);
+        s.z_b += eb;
+        if (REV) s.s2r = fmaf(eb, -d, s.s2r);
+    }
+}
+
+template <int VEC, bool REV>
+__device__ __forceinline__ void fold_chunk(LaneState &s, const float (&a)[VEC],
+                                           const float (&b)[VEC], int chunk) {
+    float cma = a[0], cmb = b[0];
+#pragma unroll
+    for (int j = 1; j < VEC; ++j) {
+        cma = fmaxf(cma, a[j]);
+        cmb = fmaxf(cmb, b[j]);
+    }
+    s.best = (cma > s.m_a) ? chunk : s.best;       // strict: the first chunk keeps a tie
+    s.m_a = fmaxf(s.m_a, cma);
+    fold<VEC, REV>(s, a, b, cma, cmb);
+}
+
+// sum_y min(P(y), Q(y)) contribution of VEC pairs; lam = log2-domain log-sum-exp
+template <int VEC>
+__device__ __forceinline__ float min_prob_sum(const float (&a)[VEC], const float (&b)[VEC],
+                                              float lam_a, float lam_b) {
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j)
+        acc += fminf(fast_exp2(fmaf(a[j], kLog2e, -lam_a)), fast_exp2(fmaf(b[j], kLog2e, -lam_b)));
+    return acc;
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+    return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ int wave_min(int x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const int other = __shfl_xor(x, off, 64);
+        x = other < x ? other : x;
+    }
+    return x;
+}
+
+// Sums of one row pair relative to the references ref_a / ref_b, plus the exact target maximum.
+struct RowTotals {
+    float ref_a, ref_b;
+    float z_a, s1, s2, z_b, s2r;
+    float row_max;
+    int arg_i;
+};
+
+// A lane's (or a partial result's) sums re-expressed relative to common references.
+__device__ __forceinline__ void to_common_reference(float rho_a, float rho_b, float ref_a,
+                                                    float ref_b, float &z_a, float &s1, float &s2,
+                                                    float &z_b, float &s2r) {
+    if (rho_a != PPOW_NEG_INF) {            // whoever saw any element saw both rows
+        const float da = rho_a - ref_a;
+        const float sa = fast_exp2(da);
+        const float sb = fast_exp2(rho_b - ref_b);
+        s1 = sa * fmaf(da, z_a, s1);
+        z_a *= sa;
+        s2 *= sa;
+        z_b *= sb;
+        s2r *= sb;
+    } else {
+        z_a = 0.f; s1 = 0.f; s2 = 0.f; z_b = 0.f; s2r = 0.f;
+    }
+}
+
+// Per-position scalars from the row totals (Sections 4.2, 4.3.2; Appendices C.1 and E), run
+// by one lane: writes the record for the window epilogue and the optional per-position outputs.
+// The drafted token of a row and the two logits it selects, loaded ahead of finish_row.
+struct DraftedToken {
+    int tok;
+    float a_tok, b_tok;
+};
+
+template <int DTYPE>
+__device__ __forceinline__ DraftedToken load_drafted_token(const RowArgs &args, int64_t row) {
+    using S = Storage<DTYPE>;
+    using elem = typename S::elem;
+    DraftedToken d;
+    d.tok = args.tokens[row];
+    d.a_tok = S::load1(static_cast<const elem *>(args.target) + row * args.V + d.tok);
+    d.b_tok = S::load1(static_cast<const elem *>(args.draft) + row * args.V + d.tok);
+    return d;
+}
+
+template <int DTYPE>
+__device__ __forceinline__ void finish_row(const RowArgs &args, int64_t row, const RowTotals &t,
+                                           float expected, const DraftedToken &drafted) {
+    const float log2_za = fast_log2(t.z_a);
+    const float log2_zb = fast_log2(t.z_b);
+    const double ln2p_d = 1.0 / static_cast<double>(kLog2e);
+    const float ln2p = static_cast<float>(ln2p_d);
+    const double inv_za = 1.0 / static_cast<double>(t.z_a);
+    const double entropy = ln2p_d * (static_cast<double>(log2_za) - t.s1 * inv_za);
+    const double lse_diff = ln2p_d * (static_cast<double>(t.ref_a - t.ref_b) +
+                                      static_cast<double>(fast_log2(t.z_a / t.z_b)));
+    const float kl = fmaxf(static_cast<float>(t.s2 * inv_za - lse_diff), 0.f);
+    float conf = static_cast<float>(1.0 - entropy * args.inv_ln_V);
+    conf = fminf(fmaxf(conf, 0.f), 1.f);
+
+    const int tok = drafted.tok;
+    const float a_tok = drafted.a_tok;
+    const float b_tok = drafted.b_tok;
+    // log-probabilities relative to the references: the error then scales with |log p|,
+    // not with the magnitude of the logits
+    const float xa = fmaf(a_tok, kLog2e, -t.ref_a) - log2_za;    // log2 P(tok)
+    const float xb = fmaf(b_tok, kLog2e, -t.ref_b) - log2_zb;    // log2 Q(tok)
+    const float logp = ln2p * xa;
+    const float logq = ln2p * xb;
+    // the ratio from the difference itself: exactly 0 when the rows are identical
+    const float log2_ratio = xa - xb;
+    const float alpha = fast_exp2(fminf(log2_ratio, 0.f));
+
+    int accept;
+    if (args.greedy) accept = (tok == t.arg_i);
+    else accept = (args.uniforms[row] <= alpha);
+
+    float reverse_kl = 0.f, alignment = 0.f;
+    if (args.want_policy_terms) {
+        const double inv_zb = 1.0 / static_cast<double>(t.z_b);
+        reverse_kl = fmaxf(static_cast<float>(t.s2r * inv_zb + lse_diff), 0.f);
+        // exp(d) - d - 1 with d = log P(tok) - log Q(tok), in double: it cancels for small d
+        const double d = ln2p_d * static_cast<double>(log2_ratio);
+        alignment = static_cast<float>(expm1(d) - d);
+    }
+
+    RowRecord rec;
+    rec.criticality = conf * kl;
+    rec.gap = t.row_max - a_tok;
+    rec.logp_tok = logp;
+    rec.accept = accept;
+    rec.reverse_kl = reverse_kl;
+    rec.alignment = alignment;
+    rec.pad0 = 0.f;
+    rec.pad1 = 0.f;
+    args.records[row] = rec;
+
+    if (args.kl) args.kl[row] = kl;
+    if (args.confidence) args.confidence[row] = conf;
+    if (args.accept_prob) args.accept_prob[row] = alpha;
+    if (args.expected_accept) args.expected_accept[row] = expected;
+    if (args.logp_target_tok) args.logp_target_tok[row] = logp;
+    if (args.logp_draft_tok) args.logp_draft_tok[row] = logq;
+    if (args.reverse_kl) args.reverse_kl[row] = reverse_kl;
+    if (args.alignment) args.alignment[row] = alignment;
+}
+
+}  // namespace ppow

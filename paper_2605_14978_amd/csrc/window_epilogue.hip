@@ -8,6 +8,8 @@
 //   delta            sum_t gap_t, or ref - sum_t log P_t(tok_t) (Section 4.3.2)
 //   r_proximity      eta * [k == 0] * [delta < eps]             (Algorithm 1)
 //   ADAW score       (1/K) sum_t v_t over all K positions       (Section 4.2)
+//   window means of KL(Q_t||P_t) (the target-anchored regulariser of Appendix A.2) and of
+//   the alignment metric of Appendix E, when asked for
 // Sums use a fixed xor-shuffle tree, so results do not depend on scheduling.
 #include "ppow_device.h"
 
@@ -23,8 +25,9 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
     const int64_t window = gid >> log2_group;
     const int t = static_cast<int>(gid & (group - 1));
     const bool active = (window < args.B) && (t < args.K);
+    if (gid == 0 && args.status_clear) *args.status_clear = 0u;
 
-    float v = 0.f, gap = 0.f, logp = 0.f;
+    float v = 0.f, gap = 0.f, logp = 0.f, rkl = 0.f, align = 0.f;
     int accept = 0;
     if (active) {
         const RowRecord rec = args.records[window * args.K + t];
@@ -32,6 +35,8 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
         gap = rec.gap;
         logp = rec.logp_tok;
         accept = rec.accept;
+        rkl = rec.reverse_kl;
+        align = rec.alignment;
     }
 
     // first rejected position of this window
@@ -47,6 +52,8 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
         v += __shfl_xor(v, off, 64);
         gap += __shfl_xor(gap, off, 64);
         logp += __shfl_xor(logp, off, 64);
+        rkl += __shfl_xor(rkl, off, 64);
+        align += __shfl_xor(align, off, 64);
     }
 
     if (active && t == 0) {
@@ -57,7 +64,29 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
         args.r_proximity[window] = (k == 0 && delta < args.prox_eps) ? args.prox_eta : 0.f;
         args.adaw_score[window] = v / static_cast<float>(args.K);
         if (args.delta) args.delta[window] = delta;
+        if (args.reverse_kl_mean) args.reverse_kl_mean[window] = rkl / static_cast<float>(args.K);
+        if (args.alignment_mean) args.alignment_mean[window] = align / static_cast<float>(args.K);
     }
+}
+
+// Group-relative advantage (Section 4.1): within each rollout group of G consecutive windows,
+// A_i = (R_i - mean) / (std + delta), R_i = r_speedup + r_proximity (Algorithm 1's reward),
+// std the population standard deviation.  One thread per group, sums in index order.
+__global__ __launch_bounds__(kThreads) void group_advantage_kernel(AdvantageArgs args) {
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (g >= args.groups) return;
+    const int64_t base = g * args.group;
+    float mean = 0.f;
+    for (int i = 0; i < args.group; ++i) mean += args.r_speedup[base + i] + args.r_proximity[base + i];
+    mean /= static_cast<float>(args.group);
+    float var = 0.f;
+    for (int i = 0; i < args.group; ++i) {
+        const float d = args.r_speedup[base + i] + args.r_proximity[base + i] - mean;
+        var = fmaf(d, d, var);
+    }
+    const float inv = 1.0f / (sqrtf(var / static_cast<float>(args.group)) + args.delta_stab);
+    for (int i = 0; i < args.group; ++i)
+        args.advantage[base + i] = (args.r_speedup[base + i] + args.r_proximity[base + i] - mean) * inv;
 }
 
 }  // namespace
@@ -70,6 +99,14 @@ hipError_t launch_window_epilogue(const WindowArgs &args, hipStream_t stream) {
     const int64_t blocks = (threads + kThreads - 1) / kThreads;
     hipLaunchKernelGGL(window_epilogue_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0,
                        stream, args, log2_group);
+    return hipGetLastError();
+}
+
+hipError_t launch_group_advantage(const AdvantageArgs &args, hipStream_t stream) {
+    if (args.groups == 0) return hipSuccess;
+    const int64_t blocks = (args.groups + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(group_advantage_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0,
+                       stream, args);
     return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@ RTOL = {"f32": 1e-4, "bf16": 2e-3}
 ATOL = 1e-6
 
 PER_POSITION = ("kl", "confidence", "accept_prob", "logp_target_tok", "logp_draft_tok")
+POLICY_TERMS = ("reverse_kl", "alignment")
 
 
 def dtype_name(t):
@@ -25,26 +26,34 @@ def dtype_name(t):
 
 
 def run_gpu(d, *, cost_ratio, verify, prox_eps=0.5, prox_eta=1.0, expected_accept=False,
-            ref_logprob=None, optional=None):
+            ref_logprob=None, optional=None, policy_terms=False, rollout_group=0, adv_delta=1e-6):
     opt = list(optional if optional is not None else ("delta",) + PER_POSITION)
     flags = 0
     if expected_accept:
         flags |= ppow.PPOW_FLAG_EXPECTED_ACCEPT
         opt.append("expected_accept")
+    if policy_terms:
+        flags |= ppow.PPOW_FLAG_POLICY_TERMS
+        opt += list(POLICY_TERMS) + ["reverse_kl_mean", "alignment_mean"]
+    if rollout_group:
+        opt.append("advantage")
     out = ppow.ppow_score_windows(
         d["draft_logits"], d["target_logits"], d["draft_tokens"], d["uniforms"], ref_logprob,
         cost_ratio=cost_ratio, prox_eps=prox_eps, prox_eta=prox_eta,
         verify=ppow.PPOW_VERIFY_GREEDY if verify == "greedy" else ppow.PPOW_VERIFY_REJECTION,
-        flags=flags, optional=tuple(opt))
+        flags=flags, rollout_group=rollout_group, adv_delta=adv_delta, optional=tuple(opt))
     torch.cuda.synchronize()
+    assert out.status() == 0, "the cluster kernel reported an expired wait"
     return out
 
 
 def run_oracle(d, *, cost_ratio, verify, prox_eps=0.5, prox_eta=1.0, expected_accept=False,
-               ref_logprob=None):
+               ref_logprob=None, policy_terms=False, **_unused):
     want = list(PER_POSITION)
     if expected_accept:
         want.append("expected_accept")
+    if policy_terms:
+        want += list(POLICY_TERMS)
     u = d["uniforms"]
     return oracle.score_windows(
         d["draft_logits"].cpu(), d["target_logits"].cpu(), d["draft_tokens"].cpu().numpy(),
@@ -83,6 +92,19 @@ def compare(gpu, ref, dname, V, expected_accept=False):
             assert_close(name, t.cpu(), getattr(ref, name), rtol, atol)
     if expected_accept:
         assert_close("expected_accept", gpu.expected_accept.cpu(), ref.expected_accept, rtol)
+    if getattr(gpu, "reverse_kl", None) is not None:
+        assert_close("reverse_kl", gpu.reverse_kl.cpu(), ref.reverse_kl, rtol)
+        assert_close("alignment", gpu.alignment.cpu(), ref.alignment, rtol)
+        assert_close("reverse_kl_mean", gpu.reverse_kl_mean.cpu(), ref.reverse_kl.mean(-1), rtol)
+        assert_close("alignment_mean", gpu.alignment_mean.cpu(), ref.alignment.mean(-1), rtol)
+
+
+def compare_advantage(gpu, ref, group, adv_delta, rtol):
+    """Group-relative advantages against the oracle's, group by group (Section 4.1)."""
+    rewards = ref.r_speedup + ref.r_proximity
+    expect = np.concatenate([oracle.group_advantage(rewards[i:i + group], adv_delta)
+                             for i in range(0, rewards.size, group)])
+    assert_close("advantage", gpu.advantage.cpu(), expect, rtol, atol=1e-5)
 
 
 def check_selection(gpu_scores, M, oracle_scores=None, rtol=None):

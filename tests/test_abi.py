@@ -21,21 +21,23 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"ppow_score_windows", "ppow_select_windows", "ppow_score_workspace_bytes",
-            "ppow_select_workspace_bytes", "ppow_last_error", "ppow_version"} <= set(names)
+            "ppow_select_workspace_bytes", "ppow_last_error", "ppow_version",
+            "ppow_last_row_kernel"} <= set(names)
     L = ppow.lib()
     for name in names:
         assert hasattr(L, name), f"{name} declared in ppow.h but not exported"
 
 
 def test_struct_layouts_match_header():
-    assert ctypes.sizeof(binding.PpowParams) == 20
-    assert ctypes.sizeof(binding.PpowOutputs) == 11 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(binding.PpowParams) == 28
+    assert ctypes.sizeof(binding.PpowOutputs) == 16 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def test_workspace_queries():
     L = ppow.lib()
-    assert L.ppow_score_workspace_bytes(16384, 8, 128256, binding.PPOW_BF16, 0) == 16384 * 8 * 16
-    assert L.ppow_score_workspace_bytes(0, 8, 128256, binding.PPOW_BF16, 0) == 256
+    scratch = 1 << 20
+    assert L.ppow_score_workspace_bytes(16384, 8, 128256, binding.PPOW_BF16, 0) == scratch + 16384 * 8 * 32
+    assert L.ppow_score_workspace_bytes(0, 8, 128256, binding.PPOW_BF16, 0) == scratch
     for bad in ((-1, 8, 100, 0), (4, 0, 100, 0), (4, 65, 100, 0), (4, 8, 1, 0), (4, 8, 100, 7),
                 (1 << 30, 8, 100, 0), (4, 8, 1 << 31, 0)):
         assert L.ppow_score_workspace_bytes(*bad, 0) == 0
@@ -46,9 +48,9 @@ def test_workspace_queries():
 
 
 def _score(L, *, draft=16, target=32, tokens=48, uniforms=64, B=4, K=2, V=100, dtype=0,
-           params=None, outs=None, ws=4096, ws_bytes=1 << 20, null_params=False, null_outs=False):
-    p = params or binding.PpowParams(0.05, 0.5, 1.0, 0, 0)
-    o = outs or binding.PpowOutputs(*( [4096] * 4 + [None] * 7))
+           params=None, outs=None, ws=4096, ws_bytes=1 << 24, null_params=False, null_outs=False):
+    p = params or binding.PpowParams(0.05, 0.5, 1.0, 0, 0, 0, 0.0)
+    o = outs or binding.PpowOutputs(*([4096] * 4 + [None] * 12))
     return L.ppow_score_windows(draft, target, tokens, uniforms, None, B, K, V, dtype,
                                 None if null_params else ctypes.byref(p),
                                 None if null_outs else ctypes.byref(o), ws, ws_bytes, None)
@@ -70,13 +72,20 @@ def test_score_argument_errors_return_before_any_launch():
     assert _score(L, target=36) == E                      # misaligned logits
     assert _score(L, uniforms=None) == E                  # rejection mode needs uniforms
     assert b"uniforms" in L.ppow_last_error()
-    assert _score(L, params=binding.PpowParams(0.0, 0.5, 1.0, 0, 0)) == E
-    assert _score(L, params=binding.PpowParams(float("nan"), 0.5, 1.0, 0, 0)) == E
-    assert _score(L, params=binding.PpowParams(0.05, 0.5, 1.0, 2, 0)) == E      # verify enum
-    assert _score(L, params=binding.PpowParams(0.05, 0.5, 1.0, 0, 8)) == E      # unknown flag
-    assert _score(L, params=binding.PpowParams(0.05, 0.5, 1.0, 0, 1)) == E      # flag w/o output
-    assert _score(L, outs=binding.PpowOutputs(*([4096] * 3 + [None] * 8))) == E
-    assert _score(L, outs=binding.PpowOutputs(*([4096] * 4 + [None] * 4 + [4096] + [None] * 2))) == E
+    P = binding.PpowParams
+    assert _score(L, params=P(0.0, 0.5, 1.0, 0, 0, 0, 0.0)) == E
+    assert _score(L, params=P(float("nan"), 0.5, 1.0, 0, 0, 0, 0.0)) == E
+    assert _score(L, params=P(0.05, 0.5, 1.0, 2, 0, 0, 0.0)) == E      # verify enum
+    assert _score(L, params=P(0.05, 0.5, 1.0, 0, 8, 0, 0.0)) == E      # unknown flag
+    assert _score(L, params=P(0.05, 0.5, 1.0, 0, 1, 0, 0.0)) == E      # flag w/o output
+    O = binding.PpowOutputs
+    assert _score(L, outs=O(*([4096] * 3 + [None] * 13))) == E           # a required output missing
+    assert _score(L, outs=O(*([4096] * 4 + [None] * 4 + [4096] + [None] * 7))) == E   # output w/o flag
+    assert _score(L, outs=O(*([4096] * 4 + [None] * 7 + [4096] + [None] * 4))) == E   # reverse_kl w/o flag
+    adv = O(*([4096] * 4 + [None] * 11 + [4096]))
+    assert _score(L, outs=adv) == E                                      # advantage w/o group size
+    assert _score(L, outs=adv, params=P(0.05, 0.5, 1.0, 0, 0, 3, 1e-6)) == E   # 3 does not divide B=4
+    assert _score(L, outs=adv, params=P(0.05, 0.5, 1.0, 0, 0, 2, -1.0)) == E
     W = binding.PPOW_ERR_WORKSPACE
     assert _score(L, ws=None) == W
     assert _score(L, ws=4100) == W

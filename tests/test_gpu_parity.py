@@ -11,7 +11,8 @@ import oracle
 import paper_2605_14978_amd as ppow
 from workloads import WORKLOADS, generate
 
-from parity import RTOL, assert_close, check_selection, compare, dtype_name, run_gpu, run_oracle
+from parity import (RTOL, assert_close, check_selection, compare, compare_advantage, dtype_name,
+                    run_gpu, run_oracle)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -204,13 +205,56 @@ def test_expected_accept_pass_small_and_ragged():
         assert np.all(ea >= 1.0 - np.sqrt(0.5 * kl) - 1e-5)          # Pinsker (Appendix B.1)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [9, 1001, 4099, 40000])
+def test_policy_terms_reverse_kl_and_alignment(V, dtype):
+    d = _random_inputs(6, 4, V, dtype, seed=3 * V + 1, sigma=1.0)
+    gpu, ref = _check(d, V, policy_terms=True)
+    assert gpu.reverse_kl is not None and float(gpu.reverse_kl.min()) >= 0
+    # the same windows with the expected-acceptance pass on top (cluster kernel variant)
+    _check(d, V, policy_terms=True, expected_accept=True)
+
+
+def test_policy_terms_vanish_for_identical_rows():
+    d = _random_inputs(3, 4, 3000, torch.bfloat16, seed=5)
+    d["draft_logits"] = d["target_logits"].clone()
+    gpu = run_gpu(d, cost_ratio=0.05, verify="rejection", policy_terms=True)
+    assert torch.all(gpu.reverse_kl == 0) and torch.all(gpu.alignment == 0)
+    assert torch.all(gpu.reverse_kl_mean == 0) and torch.all(gpu.alignment_mean == 0)
+
+
+@pytest.mark.parametrize("group", [1, 2, 8])
+def test_group_relative_advantage(group):
+    w = WORKLOADS["tiny_f32"].scaled(32)
+    d = generate(w, device=DEV)
+    ref = run_oracle(d, cost_ratio=w.cost_ratio, verify=w.verify)
+    gpu = run_gpu(d, cost_ratio=w.cost_ratio, verify=w.verify, rollout_group=group, adv_delta=1e-4)
+    compare(gpu, ref, w.dtype, w.V)
+    compare_advantage(gpu, ref, group, 1e-4, RTOL[w.dtype])
+    adv = gpu.advantage.cpu().view(-1, group)
+    assert float(adv.sum(-1).abs().max()) < 1e-4           # zero mean inside every group
+
+
+def test_second_pass_rows_longer_than_one_slice_and_many_rows_per_cluster():
+    """More row pairs than clusters, and rows long enough to be split over several members."""
+    for dtype, V in ((torch.float32, 50021), (torch.bfloat16, 70003)):
+        d = _random_inputs(150, 4, V, dtype, seed=V, sigma=0.8)
+        _check(d, V, expected_accept=True, M=20)
+        assert ppow.last_row_kernel() == "cluster"          # the LDS-resident path really ran
+        _check(d, V, M=20)
+        assert ppow.last_row_kernel() == "row"
+
+
 def test_results_are_bitwise_reproducible():
     w = WORKLOADS["rejection_bf16_128k"].scaled(16)
     d = generate(w, device=DEV)
-    outs = [run_gpu(d, cost_ratio=w.cost_ratio, verify=w.verify) for _ in range(3)]
-    for o in outs[1:]:
-        for name in ("accepted_len", "r_speedup", "r_proximity", "adaw_score", "delta", "kl"):
-            assert torch.equal(getattr(o, name), getattr(outs[0], name))
+    for extra in ({}, {"expected_accept": True, "policy_terms": True}):
+        outs = [run_gpu(d, cost_ratio=w.cost_ratio, verify=w.verify, **extra) for _ in range(3)]
+        names = ["accepted_len", "r_speedup", "r_proximity", "adaw_score", "delta", "kl"]
+        names += ["expected_accept", "reverse_kl", "alignment"] if extra else []
+        for o in outs[1:]:
+            for name in names:
+                assert torch.equal(getattr(o, name), getattr(outs[0], name)), name
 
 
 # ---- selection -----------------------------------------------------------------------------
