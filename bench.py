@@ -85,6 +85,77 @@ def measured_traffic(name):
         return json.load(fh).get(name, {}).get("bytes_per_launch")
 
 
+def bench_sequences(args, w, dev):
+    """Sequence-mode ADAW: a step scores N sequences of T positions once, forms every
+    overlapping window score, draws one start per sequence and ranks all windows."""
+    import torch
+    import paper_2605_14978_amd as ppow
+    from workloads import generate_sequences
+
+    N, T, K, V = w.B, w.seq_len, w.K, w.V
+    W = T - K + 1
+    t0 = time.perf_counter()
+    d = generate_sequences(w, device=dev)
+    torch.cuda.synchronize()
+    print(f"# generated {N} sequences of {T} positions in {time.perf_counter() - t0:.1f} s",
+          file=sys.stderr, flush=True)
+    code = ppow.PPOW_BF16 if w.dtype == "bf16" else ppow.PPOW_F32
+    buf = ppow.SequenceBuffers(N, T, V, K, code, dev)
+    selbuf = ppow.SelectBuffers(N * W, w.M, dev)
+
+    def score():
+        ppow.ppow_adaw_sequence(d["draft_logits"], d["target_logits"], K, d["uniforms"], buffers=buf)
+
+    def select():
+        ppow.ppow_select_windows(buf.window_score.view(-1), w.M, buffers=selbuf)
+
+    for _ in range(args.warmup):
+        score()
+        select()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        score()
+        stops[i].record()
+        select()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    score_ms = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) / args.steps
+    algorithmic_bytes = 2 * N * T * V * w.elem_bytes
+    achieved = algorithmic_bytes / (score_ms * 1e-3) / 1e9
+    result = {
+        "metric": "speculative windows scored/sec", "value": N * W / (ms_per_step * 1e-3),
+        "unit": "windows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "sequences": N, "positions": T, "K": K, "V": V, "M": w.M,
+                   "windows": N * W, "logit_gigabytes_per_step": algorithmic_bytes / 1e9},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(w.name),
+                     "kernel": "row_stats_kernel", "kernel_ms": score_ms,
+                     "algorithmic_bytes_per_launch": algorithmic_bytes},
+    }
+    if args.cpu_seconds > 0:
+        import numpy as np
+        import oracle
+        n = 1
+        t0 = time.perf_counter()
+        v_ref, s_ref = oracle.adaw_sequence(d["draft_logits"][:n].cpu(), d["target_logits"][:n].cpu(), K)
+        oracle.sample_starts(s_ref, d["uniforms"][:n].cpu().numpy().astype(np.float64))
+        dt = time.perf_counter() - t0
+        s_gpu = buf.window_score[:n].cpu().numpy().astype(np.float64)
+        rtol = 2e-3 if w.dtype == "bf16" else 1e-4
+        agrees = bool(np.all(np.abs(s_gpu - s_ref) <= rtol * np.abs(s_ref) + 1e-6))
+        result["cpu_baseline"] = {"value": n * W / dt, "unit": "windows/s", "cores": os.cpu_count(),
+                                  "kind": "oracle", "sample": f"first {n} of {N} sequences ({T} rows), {dt:.1f} s",
+                                  "gpu_matches_oracle_on_sample": agrees}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -120,6 +191,9 @@ def main():
     if args.expected_accept:
         w = dataclasses.replace(w, expected_accept=True)
     print(f"# {describe(w)}", file=sys.stderr, flush=True)
+
+    if w.seq_len:
+        return bench_sequences(args, w, dev)
 
     # A workload of several chunks streams them through the scoring call one after another
     # (they would not all fit in HBM); up to MAX_RESIDENT distinct chunks are kept resident and

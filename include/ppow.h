@@ -90,6 +90,10 @@ typedef struct {
                                       R_i = r_speedup + r_proximity over groups of
                                       rollout_group consecutive windows (Section 4.1);
                                       population standard deviation; needs rollout_group >= 1 */
+    int32_t *group_best_len; /* [B/G] largest accepted length among the G = rollout_group
+                                      candidate windows of a group (multi-candidate decoding,
+                                      Table 2)                                                 */
+    int32_t *group_best_index;/* [B/G] index within the group of the first window attaining it */
 } ppow_outputs;
 
 /* Bytes of device workspace ppow_score_windows needs for these sizes (0 on
@@ -129,6 +133,32 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
                        const float *ref_logprob,
                        int64_t B, int32_t K, int64_t V, int32_t dtype,
                        const ppow_params *params, const ppow_outputs *out,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device workspace ppow_adaw_sequence needs (0 on invalid sizes). */
+size_t ppow_adaw_sequence_workspace_bytes(int64_t N, int32_t T, int64_t V, int32_t dtype);
+
+/*
+ * Sequence-mode ADAW (Algorithm 1, criticality and window-selection lines): N sequences of
+ * T teacher-forced positions are scored ONCE (each logit row is read once although every
+ * position belongs to up to K overlapping windows), then
+ *   criticality[n, t]  = C(P_t) * KL(P_t || Q_t)                         t = 0..T-1
+ *   window_score[n, j] = (1/K) sum_{t=j}^{j+K-1} criticality[n, t]       j = 0..T-K
+ * and, if asked, one window start per sequence drawn with probability proportional to its
+ * window scores: the smallest j whose cumulative score reaches uniforms[n] times the total
+ * (running sums in double, index order; if all scores are zero, floor(u * (T-K+1))).
+ *
+ *   draft_logits, target_logits  [N, T, V] as in ppow_score_windows
+ *   uniforms       [N] float32 in [0,1), required iff sampled_start is given
+ *   criticality    [N*T] out or NULL;  window_score [N*(T-K+1)] out, required
+ *   sampled_start  [N] int32 out or NULL
+ *   N >= 0, 1 <= K <= T, N*T < 2^31, 2 <= V < 2^31.
+ * ppow_select_windows can then rank all N*(T-K+1) windows.
+ */
+int ppow_adaw_sequence(const void *draft_logits, const void *target_logits,
+                       int64_t N, int32_t T, int64_t V, int32_t dtype, int32_t K,
+                       const float *uniforms, float *criticality, float *window_score,
+                       int32_t *sampled_start,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Bytes of device workspace ppow_select_windows needs (0 on invalid sizes). */

@@ -77,6 +77,13 @@ def lib():
             vp, vp, _c_int32_p, _c_double_p, _c_double_p, i64, i32, i64, ctypes.c_int,
             d, d, d, ctypes.c_int, ctypes.POINTER(_Outputs), _c_int32_p]
         L.ppow_oracle_score_windows.restype = ctypes.c_int
+        L.ppow_oracle_group_best.argtypes = [_c_int32_p, i64, i32, _c_int32_p, _c_int32_p]
+        L.ppow_oracle_group_best.restype = ctypes.c_int
+        L.ppow_oracle_adaw_sequence.argtypes = [vp, vp, i64, i32, i64, ctypes.c_int, i32,
+                                                _c_double_p, _c_double_p]
+        L.ppow_oracle_adaw_sequence.restype = ctypes.c_int
+        L.ppow_oracle_sample_starts.argtypes = [_c_double_p, i64, i64, _c_double_p, _c_int64_p]
+        L.ppow_oracle_sample_starts.restype = ctypes.c_int
         L.ppow_oracle_select_windows.argtypes = [_c_double_p, i64, i64, _c_int64_p]
         L.ppow_oracle_select_windows.restype = ctypes.c_int
         _lib = L
@@ -232,6 +239,50 @@ def score_windows(draft_logits, target_logits, draft_tokens, uniforms=None, ref_
         raise ValueError("ppow_oracle_score_windows rejected its arguments")
     res.threads = int(threads.value)
     return res
+
+
+def group_best(accepted_len, group):
+    """(best accepted length, index of the first window attaining it) per group of windows."""
+    k = np.ascontiguousarray(np.asarray(accepted_len, dtype=np.int32)).reshape(-1)
+    if group < 1 or k.size % group:
+        raise ValueError("group must divide the number of windows")
+    best = np.empty(k.size // group, dtype=np.int32)
+    idx = np.empty(k.size // group, dtype=np.int32)
+    rc = lib().ppow_oracle_group_best(k.ctypes.data_as(_c_int32_p), k.size, int(group),
+                                      best.ctypes.data_as(_c_int32_p), idx.ctypes.data_as(_c_int32_p))
+    if rc != 0:
+        raise ValueError("ppow_oracle_group_best rejected its arguments")
+    return best, idx
+
+
+def adaw_sequence(draft_logits, target_logits, K):
+    """Sequence-mode ADAW: (criticality [N, T], window_score [N, T-K+1]) for [N, T, V] logits."""
+    b_bits, code_b = as_stored(draft_logits)
+    a_bits, code_a = as_stored(target_logits)
+    if code_a != code_b or a_bits.shape != b_bits.shape or a_bits.ndim != 3:
+        raise ValueError("draft and target logits must share dtype and [N, T, V] shape")
+    N, T, V = a_bits.shape
+    v = np.zeros((N, T), dtype=np.float64)
+    s = np.zeros((N, T - K + 1), dtype=np.float64)
+    rc = lib().ppow_oracle_adaw_sequence(b_bits.ctypes.data, a_bits.ctypes.data, N, T, V, code_a,
+                                         int(K), _dp(v), _dp(s))
+    if rc != 0:
+        raise ValueError("ppow_oracle_adaw_sequence rejected its arguments")
+    return v, s
+
+
+def sample_starts(score, uniforms):
+    """One window start per sequence, drawn with probability proportional to the scores."""
+    s = _f64(score)
+    if s.ndim != 2:
+        raise ValueError("score must be [N, W]")
+    u = _f64(uniforms).reshape(-1)
+    out = np.empty(s.shape[0], dtype=np.int64)
+    rc = lib().ppow_oracle_sample_starts(_dp(s), s.shape[0], s.shape[1], _dp(u),
+                                         out.ctypes.data_as(_c_int64_p))
+    if rc != 0:
+        raise ValueError("ppow_oracle_sample_starts rejected its arguments")
+    return out
 
 
 def select_windows(score, M):

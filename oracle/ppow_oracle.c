@@ -263,6 +263,99 @@ int ppow_oracle_score_windows(const void *draft_logits, const void *target_logit
     return failed ? -1 : 0;
 }
 
+int ppow_oracle_group_best(const int32_t *accepted_len, int64_t B, int32_t G,
+                           int32_t *best_len, int32_t *best_index)
+{
+    if (!accepted_len || !best_len || !best_index || G < 1 || B < 0 || B % G != 0) return -1;
+    for (int64_t g = 0; g < B / G; ++g) {
+        int32_t best = 0;
+        for (int32_t i = 1; i < G; ++i)
+            if (accepted_len[g * G + i] > accepted_len[g * G + best]) best = i;   /* first maximum */
+        best_len[g] = accepted_len[g * G + best];
+        best_index[g] = best;
+    }
+    return 0;
+}
+
+int ppow_oracle_adaw_sequence(const void *draft_logits, const void *target_logits,
+                              int64_t N, int32_t T, int64_t V, int dtype, int32_t K,
+                              double *criticality, double *window_score)
+{
+    if (!draft_logits || !target_logits || N < 0 || T < 1 || K < 1 || K > T || V < 2) return -1;
+    if (dtype != PPOW_ORACLE_F32 && dtype != PPOW_ORACLE_BF16) return -1;
+    const size_t esz = (dtype == PPOW_ORACLE_BF16) ? 2 : 4;
+    const int64_t W = (int64_t)T - K + 1;
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel
+#endif
+    {
+        double *a = (double *)malloc((size_t)V * sizeof(double));
+        double *b = (double *)malloc((size_t)V * sizeof(double));
+        double *v = (double *)malloc((size_t)T * sizeof(double));
+        if (!a || !b || !v) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp barrier
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int64_t n = 0; n < N; ++n) {
+            if (failed) continue;
+            for (int32_t t = 0; t < T; ++t) {
+                const int64_t row = n * (int64_t)T + t;
+                ppow_oracle_widen_row((const char *)target_logits + (size_t)row * (size_t)V * esz, V, dtype, a);
+                ppow_oracle_widen_row((const char *)draft_logits + (size_t)row * (size_t)V * esz, V, dtype, b);
+                const double lse_a = ppow_oracle_logsumexp(a, V);
+                const double lse_b = ppow_oracle_logsumexp(b, V);
+                const double H = ppow_oracle_entropy(a, V, lse_a);
+                v[t] = ppow_oracle_confidence(H, V) * ppow_oracle_kl(a, b, V, lse_a, lse_b);
+                if (criticality) criticality[row] = v[t];
+            }
+            if (window_score) {
+                for (int64_t j = 0; j < W; ++j) {
+                    double sum = 0.0;
+                    for (int32_t t = 0; t < K; ++t) sum += v[j + t];
+                    window_score[n * W + j] = sum / (double)K;
+                }
+            }
+        }
+        free(a);
+        free(b);
+        free(v);
+    }
+    return failed ? -1 : 0;
+}
+
+int ppow_oracle_sample_starts(const double *score, int64_t N, int64_t W, const double *uniforms,
+                              int64_t *start)
+{
+    if (!score || !uniforms || !start || N < 0 || W < 1) return -1;
+    for (int64_t n = 0; n < N; ++n) {
+        const double *s = score + n * W;
+        double total = 0.0;
+        for (int64_t j = 0; j < W; ++j) total += s[j];
+        const double u = uniforms[n];
+        if (!(total > 0.0)) {
+            int64_t j = (int64_t)floor(u * (double)W);
+            start[n] = j < W - 1 ? j : W - 1;
+            continue;
+        }
+        const double threshold = u * total;
+        double c = 0.0;
+        int64_t pick = W - 1;
+        for (int64_t j = 0; j < W; ++j) {
+            c += s[j];
+            if (c >= threshold) { pick = j; break; }
+        }
+        start[n] = pick;
+    }
+    return 0;
+}
+
 typedef struct {
     double score;
     int64_t index;

@@ -130,6 +130,36 @@ int ppow_oracle_score_windows(const void *draft_logits, const void *target_logit
                               double gamma, double eps, double eta, int verify,
                               const ppow_oracle_outputs *out, int32_t *threads_used);
 
+/* Best candidate of each group of G consecutive windows (multi-candidate speculative
+ * decoding: the candidate with the longest accepted prefix is the one that is kept;
+ * Section 4.1, Table 2): best_len[g] = max accepted length in group g, best_index[g] =
+ * index within the group of the first window attaining it.  Returns 0, or -1 on an invalid
+ * argument (G < 1, B not a multiple of G). */
+int ppow_oracle_group_best(const int32_t *accepted_len, int64_t B, int32_t G,
+                           int32_t *best_len, int32_t *best_index);
+
+/*
+ * Sequence-mode ADAW (Algorithm 1, "Compute criticality score" and "ADAW-based window
+ * selection"): for N sequences of T teacher-forced positions,
+ *   criticality[n, t]  = C(P_t) * KL(P_t || Q_t)                       t = 0..T-1
+ *   window_score[n, j] = (1/K) * sum_{t=j}^{j+K-1} criticality[n, t]   j = 0..T-K
+ * Logits are [N, T, V] in `dtype` storage.  Outputs may be NULL.  Returns 0 or -1.
+ */
+int ppow_oracle_adaw_sequence(const void *draft_logits, const void *target_logits,
+                              int64_t N, int32_t T, int64_t V, int dtype, int32_t K,
+                              double *criticality, double *window_score);
+
+/*
+ * Sample one window start per sequence from weights proportional to the window scores
+ * (Algorithm 1), by inverting the cumulative distribution with the given uniform draw u in
+ * [0,1): with c_j = sum_{i<=j} s_i, the start is the smallest j with c_j >= u * c_{W-1}
+ * (the last j if rounding leaves none).  If every score of a sequence is zero the weights
+ * are undefined and the start is drawn uniformly: floor(u * W), capped at W-1.
+ * score is [N, W]; returns 0 or -1.
+ */
+int ppow_oracle_sample_starts(const double *score, int64_t N, int64_t W, const double *uniforms,
+                              int64_t *start);
+
 /*
  * Top-M selection: the M windows with the largest score, ordered by score
  * descending and, among equal scores, by index ascending (a full stable sort,

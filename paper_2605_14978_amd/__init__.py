@@ -6,5 +6,6 @@ the thin Python binding over it.
 from .binding import (PPOW_BF16, PPOW_F32, PPOW_FLAG_EXPECTED_ACCEPT,  # noqa: F401
                       PPOW_FLAG_POLICY_TERMS,
                       PPOW_VERIFY_GREEDY, PPOW_VERIFY_REJECTION, PpowError, ScoreBuffers,
-                      SelectBuffers, last_row_kernel, lib, ppow_score_windows,
+                      SelectBuffers, SequenceBuffers, last_row_kernel, lib,
+                      ppow_adaw_sequence, ppow_score_windows,
                       ppow_select_windows)

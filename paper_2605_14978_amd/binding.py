@@ -46,7 +46,8 @@ class PpowOutputs(ctypes.Structure):
                 ("expected_accept", ctypes.c_void_p), ("logp_target_tok", ctypes.c_void_p),
                 ("logp_draft_tok", ctypes.c_void_p), ("reverse_kl", ctypes.c_void_p),
                 ("alignment", ctypes.c_void_p), ("reverse_kl_mean", ctypes.c_void_p),
-                ("alignment_mean", ctypes.c_void_p), ("advantage", ctypes.c_void_p)]
+                ("alignment_mean", ctypes.c_void_p), ("advantage", ctypes.c_void_p),
+                ("group_best_len", ctypes.c_void_p), ("group_best_index", ctypes.c_void_p)]
 
 
 class PpowError(RuntimeError):
@@ -73,6 +74,10 @@ def lib():
                                          ctypes.POINTER(PpowParams), ctypes.POINTER(PpowOutputs),
                                          vp, sz, vp]
         L.ppow_score_windows.restype = ctypes.c_int
+        L.ppow_adaw_sequence_workspace_bytes.argtypes = [i64, i32, i64, i32]
+        L.ppow_adaw_sequence_workspace_bytes.restype = sz
+        L.ppow_adaw_sequence.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.ppow_adaw_sequence.restype = ctypes.c_int
         L.ppow_select_workspace_bytes.argtypes = [i64, i32]
         L.ppow_select_workspace_bytes.restype = sz
         L.ppow_select_windows.argtypes = [vp, i64, i32, vp, vp, vp, sz, vp]
@@ -118,13 +123,15 @@ OPTIONAL_OUTPUTS = ("delta", "kl", "confidence", "accept_prob", "expected_accept
                     "logp_target_tok", "logp_draft_tok", "reverse_kl", "alignment",
                     "reverse_kl_mean", "alignment_mean", "advantage")
 PER_WINDOW_OPTIONAL = ("delta", "reverse_kl_mean", "alignment_mean", "advantage")
+PER_GROUP_OPTIONAL = ("group_best_len", "group_best_index")      # int32 [B / rollout_group]
 
 
 class ScoreBuffers:
     """Device outputs and workspace of ppow_score_windows, allocated once and reused."""
 
-    def __init__(self, B, K, V, dtype_code, device, optional=(), flags=0):
+    def __init__(self, B, K, V, dtype_code, device, optional=(), flags=0, rollout_group=0):
         self.B, self.K = B, K
+        self.rollout_group = rollout_group
         dev = torch.device(device)
         self.accepted_len = torch.empty(B, dtype=torch.int32, device=dev)
         self.r_speedup = torch.empty(B, dtype=torch.float32, device=dev)
@@ -138,6 +145,13 @@ class ScoreBuffers:
                 if name not in PER_WINDOW_OPTIONAL:
                     t = t.view(B, K)
             setattr(self, name, t)
+        for name in PER_GROUP_OPTIONAL:
+            t = None
+            if name in optional:
+                if rollout_group < 1 or B % rollout_group:
+                    raise ValueError("group outputs need rollout_group >= 1 dividing B")
+                t = torch.empty(B // rollout_group, dtype=torch.int32, device=dev)
+            setattr(self, name, t)
         nbytes = lib().ppow_score_workspace_bytes(B, K, V, dtype_code, flags)
         if nbytes == 0:
             raise PpowError(PPOW_ERR_INVALID_ARG, "sizes rejected by ppow_score_workspace_bytes")
@@ -147,9 +161,14 @@ class ScoreBuffers:
         """A view of these buffers covering windows [w0, w1) (for chunked scoring)."""
         view = object.__new__(ScoreBuffers)
         view.B, view.K = w1 - w0, self.K
+        view.rollout_group = self.rollout_group
         for name in ("accepted_len", "r_speedup", "r_proximity", "adaw_score") + OPTIONAL_OUTPUTS:
             t = getattr(self, name)
             setattr(view, name, None if t is None else t[w0:w1])
+        for name in PER_GROUP_OPTIONAL:
+            t = getattr(self, name)
+            g = max(self.rollout_group, 1)
+            setattr(view, name, None if t is None else t[w0 // g:w1 // g])
         view.workspace = self.workspace     # shared: calls on one stream run one after another
         return view
 
@@ -192,13 +211,55 @@ def ppow_score_windows(draft_logits, target_logits, draft_tokens, uniforms=None,
         raise ValueError("ref_logprob must be float32 [B]")
     code = _dtype_code(target_logits)
     if buffers is None:
-        buffers = ScoreBuffers(B, K, V, code, target_logits.device, optional, flags)
+        buffers = ScoreBuffers(B, K, V, code, target_logits.device, optional, flags, rollout_group)
     params = PpowParams(float(cost_ratio), float(prox_eps), float(prox_eta), int(verify), int(flags),
                         int(rollout_group), float(adv_delta))
     outs = buffers.as_struct()
     _check(lib().ppow_score_windows(
         _ptr(draft_logits), _ptr(target_logits), _ptr(draft_tokens), _ptr(uniforms),
         _ptr(ref_logprob), B, K, V, code, ctypes.byref(params), ctypes.byref(outs),
+        _ptr(buffers.workspace), buffers.workspace.numel(), _stream_handle(stream)))
+    return buffers
+
+
+class SequenceBuffers:
+    """Device outputs and workspace of ppow_adaw_sequence."""
+
+    def __init__(self, N, T, V, K, dtype_code, device, sample=True):
+        dev = torch.device(device)
+        self.N, self.T, self.K = N, T, K
+        self.criticality = torch.empty(N, T, dtype=torch.float32, device=dev)
+        self.window_score = torch.empty(N, T - K + 1, dtype=torch.float32, device=dev)
+        self.sampled_start = torch.empty(N, dtype=torch.int32, device=dev) if sample else None
+        nbytes = lib().ppow_adaw_sequence_workspace_bytes(N, T, V, dtype_code)
+        if nbytes == 0:
+            raise PpowError(PPOW_ERR_INVALID_ARG, "sizes rejected by ppow_adaw_sequence_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+
+def ppow_adaw_sequence(draft_logits, target_logits, K, uniforms=None, *, buffers=None, stream=None):
+    """Sequence-mode ADAW on [N, T, V] teacher-forced logits; returns the SequenceBuffers.
+
+    With `uniforms` ([N] float32) one window start per sequence is drawn in proportion to
+    the window scores.  Asynchronous on `stream` (default: torch's current stream).
+    """
+    if not target_logits.is_cuda:
+        raise RuntimeError("libppow scores device tensors only; there is no CPU path")
+    N, T, V = target_logits.shape
+    if draft_logits.shape != target_logits.shape or draft_logits.dtype != target_logits.dtype:
+        raise ValueError("draft and target logits must share shape and dtype")
+    if not (draft_logits.is_contiguous() and target_logits.is_contiguous()):
+        raise ValueError("logits must be contiguous")
+    if uniforms is not None and (uniforms.dtype != torch.float32 or uniforms.numel() != N
+                                 or not uniforms.is_contiguous()):
+        raise ValueError("uniforms must be contiguous float32 [N]")
+    code = _dtype_code(target_logits)
+    if buffers is None:
+        buffers = SequenceBuffers(N, T, V, K, code, target_logits.device, sample=uniforms is not None)
+    _check(lib().ppow_adaw_sequence(
+        _ptr(draft_logits), _ptr(target_logits), N, T, V, code, int(K), _ptr(uniforms),
+        _ptr(buffers.criticality), _ptr(buffers.window_score),
+        _ptr(buffers.sampled_start) if uniforms is not None else None,
         _ptr(buffers.workspace), buffers.workspace.numel(), _stream_handle(stream)))
     return buffers
 

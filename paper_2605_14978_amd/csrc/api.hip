@@ -88,12 +88,13 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
                           out->alignment_mean))
         return fail(PPOW_ERR_INVALID_ARG,
                     "reverse_kl / alignment outputs need PPOW_FLAG_POLICY_TERMS");
-    if (out->advantage) {
+    const bool group_outputs = out->advantage || out->group_best_len || out->group_best_index;
+    if (group_outputs) {
         if (params->rollout_group < 1 || B % params->rollout_group != 0)
             return fail(PPOW_ERR_INVALID_ARG,
-                        "advantage needs rollout_group >= 1 dividing B (got %d, B=%lld)",
+                        "group outputs need rollout_group >= 1 dividing B (got %d, B=%lld)",
                         params->rollout_group, (long long)B);
-        if (!(params->adv_delta >= 0.f) || !isfinite(params->adv_delta))
+        if (out->advantage && (!(params->adv_delta >= 0.f) || !isfinite(params->adv_delta)))
             return fail(PPOW_ERR_INVALID_ARG, "adv_delta must be a finite number >= 0");
     }
     const size_t need = ppow_score_workspace_bytes(B, K, V, dtype, params->flags);
@@ -159,19 +160,76 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     if (err != hipSuccess)
         return fail(PPOW_ERR_DEVICE, "window kernel launch failed: %s", hipGetErrorString(err));
 
-    if (out->advantage) {
-        ppow::AdvantageArgs aa;
-        aa.r_speedup = out->r_speedup;
-        aa.r_proximity = out->r_proximity;
-        aa.advantage = out->advantage;
-        aa.group = params->rollout_group;
-        aa.groups = B / params->rollout_group;
-        aa.delta_stab = params->adv_delta;
-        err = ppow::launch_group_advantage(aa, stream);
+    if (group_outputs) {
+        ppow::GroupArgs ga;
+        ga.r_speedup = out->r_speedup;
+        ga.r_proximity = out->r_proximity;
+        ga.accepted_len = out->accepted_len;
+        ga.advantage = out->advantage;
+        ga.best_len = out->group_best_len;
+        ga.best_index = out->group_best_index;
+        ga.group = params->rollout_group;
+        ga.groups = B / params->rollout_group;
+        ga.delta_stab = params->adv_delta;
+        err = ppow::launch_group_epilogue(ga, stream);
         if (err != hipSuccess)
-            return fail(PPOW_ERR_DEVICE, "advantage kernel launch failed: %s",
-                        hipGetErrorString(err));
+            return fail(PPOW_ERR_DEVICE, "group kernel launch failed: %s", hipGetErrorString(err));
     }
+    return PPOW_OK;
+}
+
+size_t ppow_adaw_sequence_workspace_bytes(int64_t N, int32_t T, int64_t V, int32_t dtype) {
+    if (N < 0 || T < 1 || V < 2 || V > INT32_MAX || N > INT32_MAX / T) return 0;
+    if (dtype != PPOW_F32 && dtype != PPOW_BF16) return 0;
+    return ppow::kClusterScratchBytes +
+           static_cast<size_t>(N) * static_cast<size_t>(T) * sizeof(ppow::RowRecord);
+}
+
+int ppow_adaw_sequence(const void *draft_logits, const void *target_logits, int64_t N, int32_t T,
+                       int64_t V, int32_t dtype, int32_t K, const float *uniforms,
+                       float *criticality, float *window_score, int32_t *sampled_start,
+                       void *workspace, size_t workspace_bytes, void *hip_stream) {
+    const size_t need = ppow_adaw_sequence_workspace_bytes(N, T, V, dtype);
+    if (need == 0 || K < 1 || K > T)
+        return fail(PPOW_ERR_INVALID_ARG,
+                    "sizes out of range: N=%lld T=%d V=%lld K=%d dtype=%d (need N>=0, 1<=K<=T, "
+                    "N*T<2^31, 2<=V<2^31, dtype f32|bf16)",
+                    (long long)N, T, (long long)V, K, dtype);
+    if (N == 0) return PPOW_OK;
+    if (!draft_logits || !target_logits || !window_score)
+        return fail(PPOW_ERR_INVALID_ARG, "logits and window_score must not be NULL");
+    if (!aligned16(draft_logits) || !aligned16(target_logits))
+        return fail(PPOW_ERR_INVALID_ARG, "logit base pointers must be 16-byte aligned");
+    if (sampled_start && !uniforms)
+        return fail(PPOW_ERR_INVALID_ARG, "sampled_start needs uniforms");
+    if (!workspace || !aligned16(workspace) || workspace_bytes < need)
+        return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    ppow::RowArgs ra = {};
+    ra.target = target_logits;
+    ra.draft = draft_logits;
+    ra.records = reinterpret_cast<ppow::RowRecord *>(static_cast<char *>(workspace) +
+                                                      ppow::kClusterScratchBytes);
+    ra.V = V;
+    ra.inv_ln_V = 1.0 / log(static_cast<double>(V));
+    g_row_kernel = "row";
+    hipError_t err = ppow::launch_row_stats(ra, N * T, dtype, stream);
+    if (err != hipSuccess)
+        return fail(PPOW_ERR_DEVICE, "row kernel launch failed: %s", hipGetErrorString(err));
+
+    ppow::SequenceArgs sa;
+    sa.records = ra.records;
+    sa.uniforms = uniforms;
+    sa.criticality = criticality;
+    sa.window_score = window_score;
+    sa.sampled_start = sampled_start;
+    sa.N = N;
+    sa.T = T;
+    sa.K = K;
+    err = ppow::launch_sequence_windows(sa, stream);
+    if (err != hipSuccess)
+        return fail(PPOW_ERR_DEVICE, "sequence kernel launch failed: %s", hipGetErrorString(err));
     return PPOW_OK;
 }
 

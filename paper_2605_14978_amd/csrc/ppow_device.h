@@ -58,13 +58,26 @@ struct WindowArgs {
     float cost_ratio, prox_eps, prox_eta;
 };
 
-struct AdvantageArgs {
+struct GroupArgs {
     const float *r_speedup;      // [B]
     const float *r_proximity;    // [B]
-    float *advantage;            // [B]
+    const int32_t *accepted_len; // [B]
+    float *advantage;            // [B] or nullptr
+    int32_t *best_len;           // [B / group] or nullptr
+    int32_t *best_index;         // [B / group] or nullptr
     int64_t groups;              // B / group
-    int32_t group;               // rollout group size G
+    int32_t group;               // rollout / candidate group size G
     float delta_stab;            // small positive constant of the normalisation
+};
+
+struct SequenceArgs {
+    const RowRecord *records;    // [N*T]
+    const float *uniforms;       // [N] or nullptr
+    float *criticality;          // [N*T] or nullptr
+    float *window_score;         // [N*(T-K+1)]
+    int32_t *sampled_start;      // [N] or nullptr
+    int64_t N;
+    int32_t T, K;
 };
 
 // Scratch words of the cluster variant of the row kernel, kept in front of the records.
@@ -74,7 +87,8 @@ hipError_t launch_row_stats(const RowArgs &args, int64_t rows, int32_t dtype, hi
 hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, void *scratch,
                               hipStream_t stream, bool *launched);
 hipError_t launch_window_epilogue(const WindowArgs &args, hipStream_t stream);
-hipError_t launch_group_advantage(const AdvantageArgs &args, hipStream_t stream);
+hipError_t launch_group_epilogue(const GroupArgs &args, hipStream_t stream);
+hipError_t launch_sequence_windows(const SequenceArgs &args, hipStream_t stream);
 
 size_t select_workspace_bytes(int64_t B, int32_t M);
 hipError_t launch_select(const float *score, int64_t B, int32_t M, int32_t *indices, float *scores,

@@ -219,6 +219,10 @@ __device__ __forceinline__ DraftedToken load_drafted_token(const RowArgs &args, 
     using S = Storage<DTYPE>;
     using elem = typename S::elem;
     DraftedToken d;
+    if (!args.tokens) {                   // sequence mode: no drafted token to verify
+        d.tok = -1; d.a_tok = 0.f; d.b_tok = 0.f;
+        return d;
+    }
     d.tok = args.tokens[row];
     d.a_tok = S::load1(static_cast<const elem *>(args.target) + row * args.V + d.tok);
     d.b_tok = S::load1(static_cast<const elem *>(args.draft) + row * args.V + d.tok);
@@ -253,9 +257,11 @@ __device__ __forceinline__ void finish_row(const RowArgs &args, int64_t row, con
     const float log2_ratio = xa - xb;
     const float alpha = fast_exp2(fminf(log2_ratio, 0.f));
 
-    int accept;
-    if (args.greedy) accept = (tok == t.arg_i);
-    else accept = (args.uniforms[row] <= alpha);
+    int accept = 0;
+    if (tok >= 0) {
+        if (args.greedy) accept = (tok == t.arg_i);
+        else accept = (args.uniforms[row] <= alpha);
+    }
 
     float reverse_kl = 0.f, alignment = 0.f;
     if (args.want_policy_terms) {

@@ -69,24 +69,78 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
     }
 }
 
-// Group-relative advantage (Section 4.1): within each rollout group of G consecutive windows,
-// A_i = (R_i - mean) / (std + delta), R_i = r_speedup + r_proximity (Algorithm 1's reward),
-// std the population standard deviation.  One thread per group, sums in index order.
-__global__ __launch_bounds__(kThreads) void group_advantage_kernel(AdvantageArgs args) {
+// Per group of G consecutive windows, one thread per group, everything in index order:
+//  * group-relative advantage (Section 4.1): A_i = (R_i - mean) / (std + delta) with
+//    R_i = r_speedup + r_proximity (Algorithm 1's reward), std the population standard deviation;
+//  * best candidate (multi-candidate decoding, Table 2): the largest accepted length of the
+//    group and the index of the first window attaining it.
+__global__ __launch_bounds__(kThreads) void group_epilogue_kernel(GroupArgs args) {
     const int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (g >= args.groups) return;
     const int64_t base = g * args.group;
-    float mean = 0.f;
-    for (int i = 0; i < args.group; ++i) mean += args.r_speedup[base + i] + args.r_proximity[base + i];
-    mean /= static_cast<float>(args.group);
-    float var = 0.f;
-    for (int i = 0; i < args.group; ++i) {
-        const float d = args.r_speedup[base + i] + args.r_proximity[base + i] - mean;
-        var = fmaf(d, d, var);
+    if (args.advantage) {
+        float mean = 0.f;
+        for (int i = 0; i < args.group; ++i) mean += args.r_speedup[base + i] + args.r_proximity[base + i];
+        mean /= static_cast<float>(args.group);
+        float var = 0.f;
+        for (int i = 0; i < args.group; ++i) {
+            const float d = args.r_speedup[base + i] + args.r_proximity[base + i] - mean;
+            var = fmaf(d, d, var);
+        }
+        const float inv = 1.0f / (sqrtf(var / static_cast<float>(args.group)) + args.delta_stab);
+        for (int i = 0; i < args.group; ++i)
+            args.advantage[base + i] =
+                (args.r_speedup[base + i] + args.r_proximity[base + i] - mean) * inv;
     }
-    const float inv = 1.0f / (sqrtf(var / static_cast<float>(args.group)) + args.delta_stab);
-    for (int i = 0; i < args.group; ++i)
-        args.advantage[base + i] = (args.r_speedup[base + i] + args.r_proximity[base + i] - mean) * inv;
+    if (args.best_len || args.best_index) {
+        int best = 0, best_k = args.accepted_len[base];
+        for (int i = 1; i < args.group; ++i) {
+            const int k = args.accepted_len[base + i];
+            if (k > best_k) { best_k = k; best = i; }
+        }
+        if (args.best_len) args.best_len[g] = best_k;
+        if (args.best_index) args.best_index[g] = best;
+    }
+}
+
+// Sequence-mode ADAW (Algorithm 1): one workgroup per sequence of T scored positions.
+//   window_score[j] = (1/K) sum_{t=j}^{j+K-1} v_t, summed in index order;
+//   sampled start: inverse of the cumulative distribution of the window scores at the given
+//   uniform draw, the running sum kept in double and in index order (so the decision is the
+//   one a double-precision reference takes on the same fp32 scores); all-zero scores fall
+//   back to a uniform draw floor(u * W).
+__global__ __launch_bounds__(kThreads) void sequence_windows_kernel(SequenceArgs args) {
+    const int64_t n = blockIdx.x;
+    const int T = args.T, K = args.K, W = T - K + 1;
+    const RowRecord *rec = args.records + n * T;
+    if (args.criticality)
+        for (int t = threadIdx.x; t < T; t += kThreads) args.criticality[n * T + t] = rec[t].criticality;
+    float *score = args.window_score + n * W;
+    for (int j = threadIdx.x; j < W; j += kThreads) {
+        float sum = 0.f;
+        for (int t = 0; t < K; ++t) sum += rec[j + t].criticality;
+        score[j] = sum / static_cast<float>(K);
+    }
+    if (!args.sampled_start) return;
+    __syncthreads();                        // the scores of this sequence are all written
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+        for (int j = 0; j < W; ++j) total += static_cast<double>(score[j]);
+        const double u = static_cast<double>(args.uniforms[n]);
+        int pick = W - 1;
+        if (!(total > 0.0)) {
+            const int j = static_cast<int>(floor(u * static_cast<double>(W)));
+            pick = j < W - 1 ? j : W - 1;
+        } else {
+            const double threshold = u * total;
+            double c = 0.0;
+            for (int j = 0; j < W; ++j) {
+                c += static_cast<double>(score[j]);
+                if (c >= threshold) { pick = j; break; }
+            }
+        }
+        args.sampled_start[n] = pick;
+    }
 }
 
 }  // namespace
@@ -102,10 +156,17 @@ hipError_t launch_window_epilogue(const WindowArgs &args, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_group_advantage(const AdvantageArgs &args, hipStream_t stream) {
+hipError_t launch_group_epilogue(const GroupArgs &args, hipStream_t stream) {
     if (args.groups == 0) return hipSuccess;
     const int64_t blocks = (args.groups + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL(group_advantage_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0,
+    hipLaunchKernelGGL(group_epilogue_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0,
+                       stream, args);
+    return hipGetLastError();
+}
+
+hipError_t launch_sequence_windows(const SequenceArgs &args, hipStream_t stream) {
+    if (args.N == 0) return hipSuccess;
+    hipLaunchKernelGGL(sequence_windows_kernel, dim3(static_cast<unsigned>(args.N)), dim3(kThreads), 0,
                        stream, args);
     return hipGetLastError();
 }

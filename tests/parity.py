@@ -36,7 +36,7 @@ def run_gpu(d, *, cost_ratio, verify, prox_eps=0.5, prox_eta=1.0, expected_accep
         flags |= ppow.PPOW_FLAG_POLICY_TERMS
         opt += list(POLICY_TERMS) + ["reverse_kl_mean", "alignment_mean"]
     if rollout_group:
-        opt.append("advantage")
+        opt += ["advantage", "group_best_len", "group_best_index"]
     out = ppow.ppow_score_windows(
         d["draft_logits"], d["target_logits"], d["draft_tokens"], d["uniforms"], ref_logprob,
         cost_ratio=cost_ratio, prox_eps=prox_eps, prox_eta=prox_eta,
@@ -97,6 +97,13 @@ def compare(gpu, ref, dname, V, expected_accept=False):
         assert_close("alignment", gpu.alignment.cpu(), ref.alignment, rtol)
         assert_close("reverse_kl_mean", gpu.reverse_kl_mean.cpu(), ref.reverse_kl.mean(-1), rtol)
         assert_close("alignment_mean", gpu.alignment_mean.cpu(), ref.alignment.mean(-1), rtol)
+
+
+def compare_group_best(gpu, ref, group):
+    """Best candidate per group: exact."""
+    best, idx = oracle.group_best(ref.accepted_len, group)
+    assert np.array_equal(gpu.group_best_len.cpu().numpy(), best)
+    assert np.array_equal(gpu.group_best_index.cpu().numpy(), idx)
 
 
 def compare_advantage(gpu, ref, group, adv_delta, rtol):

@@ -22,7 +22,8 @@ def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"ppow_score_windows", "ppow_select_windows", "ppow_score_workspace_bytes",
             "ppow_select_workspace_bytes", "ppow_last_error", "ppow_version",
-            "ppow_last_row_kernel"} <= set(names)
+            "ppow_last_row_kernel", "ppow_adaw_sequence",
+            "ppow_adaw_sequence_workspace_bytes"} <= set(names)
     L = ppow.lib()
     for name in names:
         assert hasattr(L, name), f"{name} declared in ppow.h but not exported"
@@ -30,7 +31,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(binding.PpowParams) == 28
-    assert ctypes.sizeof(binding.PpowOutputs) == 16 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(binding.PpowOutputs) == 18 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def test_workspace_queries():
@@ -50,7 +51,7 @@ def test_workspace_queries():
 def _score(L, *, draft=16, target=32, tokens=48, uniforms=64, B=4, K=2, V=100, dtype=0,
            params=None, outs=None, ws=4096, ws_bytes=1 << 24, null_params=False, null_outs=False):
     p = params or binding.PpowParams(0.05, 0.5, 1.0, 0, 0, 0, 0.0)
-    o = outs or binding.PpowOutputs(*([4096] * 4 + [None] * 12))
+    o = outs or binding.PpowOutputs(*([4096] * 4 + [None] * 14))
     return L.ppow_score_windows(draft, target, tokens, uniforms, None, B, K, V, dtype,
                                 None if null_params else ctypes.byref(p),
                                 None if null_outs else ctypes.byref(o), ws, ws_bytes, None)
@@ -79,10 +80,11 @@ def test_score_argument_errors_return_before_any_launch():
     assert _score(L, params=P(0.05, 0.5, 1.0, 0, 8, 0, 0.0)) == E      # unknown flag
     assert _score(L, params=P(0.05, 0.5, 1.0, 0, 1, 0, 0.0)) == E      # flag w/o output
     O = binding.PpowOutputs
-    assert _score(L, outs=O(*([4096] * 3 + [None] * 13))) == E           # a required output missing
-    assert _score(L, outs=O(*([4096] * 4 + [None] * 4 + [4096] + [None] * 7))) == E   # output w/o flag
-    assert _score(L, outs=O(*([4096] * 4 + [None] * 7 + [4096] + [None] * 4))) == E   # reverse_kl w/o flag
-    adv = O(*([4096] * 4 + [None] * 11 + [4096]))
+    assert _score(L, outs=O(*([4096] * 3 + [None] * 15))) == E           # a required output missing
+    assert _score(L, outs=O(*([4096] * 4 + [None] * 4 + [4096] + [None] * 9))) == E   # output w/o flag
+    assert _score(L, outs=O(*([4096] * 4 + [None] * 7 + [4096] + [None] * 6))) == E   # reverse_kl w/o flag
+    assert _score(L, outs=O(*([4096] * 4 + [None] * 12 + [4096, None]))) == E        # group output w/o group
+    adv = O(*([4096] * 4 + [None] * 11 + [4096] + [None] * 2))
     assert _score(L, outs=adv) == E                                      # advantage w/o group size
     assert _score(L, outs=adv, params=P(0.05, 0.5, 1.0, 0, 0, 3, 1e-6)) == E   # 3 does not divide B=4
     assert _score(L, outs=adv, params=P(0.05, 0.5, 1.0, 0, 0, 2, -1.0)) == E
@@ -91,6 +93,23 @@ def test_score_argument_errors_return_before_any_launch():
     assert _score(L, ws=4100) == W
     assert _score(L, ws_bytes=8) == W
     assert b"workspace" in L.ppow_last_error()
+
+
+def test_sequence_argument_errors_return_before_any_launch():
+    L = ppow.lib()
+    E, W = binding.PPOW_ERR_INVALID_ARG, binding.PPOW_ERR_WORKSPACE
+
+    def seq(draft=16, target=32, N=2, T=8, V=100, dtype=0, K=4, u=None, crit=None, score=4096,
+            start=None, ws=4096, ws_bytes=1 << 24):
+        return L.ppow_adaw_sequence(draft, target, N, T, V, dtype, K, u, crit, score, start, ws,
+                                    ws_bytes, None)
+    assert L.ppow_adaw_sequence_workspace_bytes(64, 2048, 128256, 1) == (1 << 20) + 64 * 2048 * 32
+    assert L.ppow_adaw_sequence_workspace_bytes(2, 0, 100, 0) == 0
+    assert seq(K=0) == E and seq(K=9) == E and seq(T=0) == E and seq(V=1) == E and seq(dtype=3) == E
+    assert seq(N=-1) == E and seq(draft=None) == E and seq(score=None) == E and seq(target=40) == E
+    assert seq(start=4096) == E                      # sampling needs uniforms
+    assert seq(ws=None) == W and seq(ws_bytes=64) == W
+    assert seq(N=0, draft=None, target=None, score=None) == binding.PPOW_OK
 
 
 def test_select_argument_errors_return_before_any_launch():

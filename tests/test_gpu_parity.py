@@ -11,7 +11,8 @@ import oracle
 import paper_2605_14978_amd as ppow
 from workloads import WORKLOADS, generate
 
-from parity import (RTOL, assert_close, check_selection, compare, compare_advantage, dtype_name,
+from parity import (RTOL, assert_close, check_selection, compare, compare_advantage,
+                    compare_group_best, dtype_name,
                     run_gpu, run_oracle)
 
 pytestmark = pytest.mark.gpu
@@ -231,8 +232,80 @@ def test_group_relative_advantage(group):
     gpu = run_gpu(d, cost_ratio=w.cost_ratio, verify=w.verify, rollout_group=group, adv_delta=1e-4)
     compare(gpu, ref, w.dtype, w.V)
     compare_advantage(gpu, ref, group, 1e-4, RTOL[w.dtype])
+    compare_group_best(gpu, ref, group)
     adv = gpu.advantage.cpu().view(-1, group)
     assert float(adv.sum(-1).abs().max()) < 1e-4           # zero mean inside every group
+
+
+def test_group_best_with_ties_takes_the_first_candidate():
+    K, V = 4, 300
+    d = _random_inputs(12, K, V, torch.float32, seed=21, greedy=True)
+    ystar = d["target_logits"].argmax(-1).to(torch.int32)
+    tok = ystar.clone()
+    lens = [0, 2, 2, 1, 4, 4, 3, 4, 1, 1, 0, 1]          # groups of 4: best 2@1, 4@0, 1@0
+    for b, k in enumerate(lens):
+        if k < K:
+            tok[b, k] = (ystar[b, k] + 1) % V
+    d["draft_tokens"] = tok.contiguous()
+    gpu = run_gpu(d, cost_ratio=0.1, verify="greedy", rollout_group=4)
+    assert gpu.accepted_len.cpu().tolist() == lens
+    assert gpu.group_best_len.cpu().tolist() == [2, 4, 1]
+    assert gpu.group_best_index.cpu().tolist() == [1, 0, 0]
+
+
+# ---- sequence-mode ADAW (Algorithm 1) ---------------------------------------------------------
+
+def _sequence_inputs(N, T, V, dtype, seed, sigma=0.8):
+    g = torch.Generator().manual_seed(seed)
+    a = torch.randn(N, T, V, generator=g) * 3.0
+    sig = torch.rand(N, T, 1, generator=g) * sigma * 2
+    b = a + torch.randn(N, T, V, generator=g) * sig
+    return a.to(dtype).to(DEV), b.to(dtype).to(DEV), torch.rand(N, generator=g).to(DEV)
+
+
+@pytest.mark.parametrize("N,T,V,K,dtype", [(3, 12, 1001, 4, torch.float32), (2, 40, 4099, 10, torch.bfloat16),
+                                           (5, 7, 300, 7, torch.float32), (4, 9, 515, 1, torch.bfloat16),
+                                           (1, 300, 2000, 64, torch.float32)])
+def test_sequence_mode_matches_oracle(N, T, V, K, dtype):
+    a, b, u = _sequence_inputs(N, T, V, dtype, seed=N * 1000 + T)
+    out = ppow.ppow_adaw_sequence(b, a, K, u)
+    torch.cuda.synchronize()
+    v_ref, s_ref = oracle.adaw_sequence(b.cpu(), a.cpu(), K)
+    rtol = RTOL[dtype_name(a)]
+    assert_close("criticality", out.criticality.cpu(), v_ref, rtol)
+    assert_close("window_score", out.window_score.cpu(), s_ref, rtol)
+    # the sampler is exact on the scores the GPU itself produced ...
+    s_gpu = out.window_score.cpu().numpy().astype(np.float64)
+    picks = oracle.sample_starts(s_gpu, u.cpu().numpy().astype(np.float64))
+    assert np.array_equal(out.sampled_start.cpu().numpy(), picks)
+    # ... and agrees with the oracle end to end wherever the draw is not within the float
+    # tolerance of a boundary of the cumulative distribution
+    c = np.cumsum(s_ref, axis=1)
+    thr = u.cpu().numpy().astype(np.float64) * c[:, -1]
+    clear = np.abs(c - thr[:, None]).min(1) > 10 * rtol * c[:, -1]
+    ref_picks = oracle.sample_starts(s_ref, u.cpu().numpy().astype(np.float64))
+    assert np.array_equal(out.sampled_start.cpu().numpy()[clear], ref_picks[clear])
+    # scoring the overlapping windows one by one gives the same scores (K x the bytes)
+    if T <= 40:
+        W = T - K + 1
+        wa = torch.stack([a[n, j:j + K] for n in range(N) for j in range(W)]).contiguous()
+        wb = torch.stack([b[n, j:j + K] for n in range(N) for j in range(W)]).contiguous()
+        d = {"target_logits": wa, "draft_logits": wb, "uniforms": torch.ones(N * W, K, device=DEV),
+             "draft_tokens": torch.zeros(N * W, K, dtype=torch.int32, device=DEV)}
+        win = run_gpu(d, cost_ratio=0.1, verify="rejection")
+        assert_close("window mode", win.adaw_score.cpu(), out.window_score.cpu().reshape(-1), 1e-5)
+
+
+def test_sequence_mode_degenerate_scores_sample_uniformly():
+    a, _, _ = _sequence_inputs(2, 10, 200, torch.float32, seed=9)
+    u = torch.tensor([0.0, 0.73], device=DEV)
+    out = ppow.ppow_adaw_sequence(a.clone(), a, 3, u)          # identical rows: every score is zero
+    torch.cuda.synchronize()
+    assert torch.all(out.window_score == 0)
+    assert out.sampled_start.cpu().tolist() == [0, int(0.73 * 8)]
+    no_sampling = ppow.ppow_adaw_sequence(a.clone(), a, 3)
+    torch.cuda.synchronize()
+    assert no_sampling.sampled_start is None and torch.all(no_sampling.criticality == 0)
 
 
 def test_second_pass_rows_longer_than_one_slice_and_many_rows_per_cluster():

@@ -381,3 +381,50 @@ def test_group_advantage_is_standardised():
     assert np.array_equal(np.argsort(adv), np.argsort(r))          # order preserved
     np.testing.assert_allclose(adv, (r - r.mean()) / (r.std() + 1e-6), rtol=1e-12)
     assert np.all(oracle.group_advantage(np.full(8, 2.5), 1e-6) == 0.0)
+
+
+# ---- candidate groups and sequence-mode ADAW (Algorithm 1) -----------------------------------
+
+def test_group_best_is_first_maximum():
+    k = [0, 3, 3, 1, 2, 2, 2, 2, 5, 0, 0, 0]
+    best, idx = oracle.group_best(k, 4)
+    assert list(best) == [3, 2, 5] and list(idx) == [1, 0, 0]
+    best, idx = oracle.group_best(k, 1)
+    assert list(best) == k and list(idx) == [0] * 12
+    with pytest.raises(ValueError):
+        oracle.group_best(k, 5)
+
+
+def test_sequence_scores_match_independent_windows():
+    """Scoring T rows once and box-filtering must equal scoring every overlapping window
+    on its own (the definition of s_j in Section 4.2)."""
+    rng = np.random.default_rng(30)
+    N, T, V, K = 2, 9, 200, 4
+    a = rng.normal(0, 3, size=(N, T, V)).astype(np.float32)
+    b = (a + rng.normal(0, 1, size=a.shape)).astype(np.float32)
+    v, s = oracle.adaw_sequence(b, a, K)
+    assert v.shape == (N, T) and s.shape == (N, T - K + 1)
+    # every overlapping window as an independent [K, V] window of the window-mode scorer
+    wa = np.stack([a[n, j:j + K] for n in range(N) for j in range(T - K + 1)])
+    wb = np.stack([b[n, j:j + K] for n in range(N) for j in range(T - K + 1)])
+    r = oracle.score_windows(wb, wa, np.zeros((wa.shape[0], K), np.int64), np.ones((wa.shape[0], K)),
+                             cost_ratio=0.1)
+    np.testing.assert_allclose(s.reshape(-1), r.adaw_score, rtol=1e-13)
+    np.testing.assert_allclose(v[0, :K], r.confidence[0] * r.kl[0], rtol=1e-13)
+    # box filter closed form: s_{j+1} - s_j = (v_{j+K} - v_j) / K
+    np.testing.assert_allclose(np.diff(s, axis=1), (v[:, K:] - v[:, :-K]) / K, rtol=1e-9, atol=1e-14)
+
+
+def test_sample_starts_inverts_the_cumulative_distribution():
+    s = np.array([[1.0, 0.0, 3.0, 0.0, 4.0], [0.0, 0.0, 0.0, 0.0, 0.0], [0.0, 2.0, 0.0, 0.0, 0.0]])
+    # sequence 0: cumulative shares 0.125, 0.125, 0.5, 0.5, 1.0
+    for u, expect in ((0.0, 0), (0.1, 0), (0.125, 0), (0.126, 2), (0.5, 2), (0.51, 4), (0.999, 4)):
+        assert oracle.sample_starts(s[:1], [u])[0] == expect
+    # all-zero scores: uniform over the W starts; a single nonzero score: always that start
+    assert [oracle.sample_starts(s[1:2], [u])[0] for u in (0.0, 0.39, 0.4, 0.99)] == [0, 1, 2, 4]
+    assert [oracle.sample_starts(s[2:3], [u])[0] for u in (0.001, 0.5, 0.999)] == [1, 1, 1]
+    # frequencies over a fine grid of u approach the normalised weights
+    u = (np.arange(8000) + 0.5) / 8000
+    picks = oracle.sample_starts(np.repeat(s[:1], u.size, 0), u)
+    freq = np.bincount(picks, minlength=5) / u.size
+    np.testing.assert_allclose(freq, s[0] / s[0].sum(), atol=2e-4)

@@ -26,6 +26,7 @@ class Workload:
     expected_accept: bool = False   # also run the normalised-probability pass
     prox_eps: float = 0.5
     prox_eta: float = 1.0
+    seq_len: int = 0      # > 0: sequence mode, B sequences of seq_len teacher-forced positions
 
     @property
     def elem_bytes(self) -> int:
@@ -54,6 +55,11 @@ WORKLOADS = {
     "stream_bf16_128k": Workload("stream_bf16_128k", "bf16", 8192, 10, 128256, "rejection", 0.03,
                                  8192, 4000, "zipf", chunks=8),
 }
+
+# Sequence-mode ADAW (Algorithm 1): 64 responses of 2048 positions, every overlapping window of
+# K = 10 scored from one pass over the rows.
+WORKLOADS["sequence_bf16_128k"] = Workload("sequence_bf16_128k", "bf16", 64, 10, 128256, "rejection",
+                                           0.03, 2048, 5, "zipf", seq_len=2048)
 
 # order of the benchmark's configuration list: index 1 is the greedy 32K case
 ORDER = ["tiny_f32", "greedy_bf16_32k", "rejection_bf16_128k", "twopass_f32_152k",

@@ -162,6 +162,17 @@ def generate(w: Workload, device="cpu", chunk: int = 0):
     }
 
 
+def generate_sequences(w: Workload, device="cpu"):
+    """Inputs of sequence-mode ADAW: [N, T, V] teacher-forced logits and one uniform per sequence."""
+    from dataclasses import replace
+    as_windows = replace(w, K=w.seq_len, seq_len=0)           # one "window" per sequence
+    d = generate(as_windows, device=device)
+    gen = torch.Generator(device=torch.device(device))
+    gen.manual_seed(w.seed + 7919)
+    return {"target_logits": d["target_logits"], "draft_logits": d["draft_logits"],
+            "uniforms": torch.rand(w.B, generator=gen, device=device)}
+
+
 def accepted_length_histogram(accepted_len, K):
     """Counts of windows by accepted length 0..K (a report, not a check)."""
     return torch.bincount(accepted_len.to(torch.int64).cpu(), minlength=K + 1).tolist()
