@@ -18,6 +18,7 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 constexpr int kLdsSortCap = 8192;          // composites the LDS sort buffer holds (64 KiB)
+constexpr int kBatch = 4;                  // scores a lane fetches before it processes them
 
 __device__ __forceinline__ uint32_t ordered_bits(float x) {
     uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
                                                           uint64_t *global_buf) {
     __shared__ uint64_t lds_buf[SORT_IN_LDS ? kLdsSortCap : 1];
     __shared__ uint32_t hist[kWaves][256];
-    __shared__ uint32_t sh_digit, sh_need, sh_count;
+    __shared__ uint32_t sh_digit, sh_need, sh_count, sh_bin;
     uint64_t *buf = SORT_IN_LDS ? lds_buf : global_buf;
 
     const int tid = threadIdx.x;
@@ -60,9 +61,34 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
         }
         for (int i = tid; i < kWaves * 256; i += kThreads) (&hist[0][0])[i] = 0;
         __syncthreads();
-        for (int i = tid; i < B; i += kThreads) {
-            const uint64_t c = composite(score[i], i);
-            if ((c & prefix_mask) == prefix) atomicAdd(&hist[wave][(c >> shift) & 0xff], 1u);
+        for (int i0 = 0; i0 < B; i0 += kBatch * kThreads) {
+            float key[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {               // kBatch independent loads in flight
+                const int i = i0 + u * kThreads + tid;
+                key[u] = i < B ? score[i] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int i = i0 + u * kThreads + tid;
+                const bool valid = i < B;
+                const uint64_t c = valid ? composite(key[u], i) : 0;
+                const bool match = valid && (c & prefix_mask) == prefix;
+                const uint32_t digit = static_cast<uint32_t>(c >> shift) & 0xffu;
+                // Scores crowd into few leading digits: the lanes that share the digit of the
+                // first matching lane are counted with one LDS atomic instead of up to 64
+                // colliding ones.
+                const unsigned long long matching = __ballot(match);
+                if (matching) {
+                    const int leader = __ffsll(static_cast<long long>(matching)) - 1;
+                    const uint32_t d0 = __shfl(digit, leader, 64);
+                    const unsigned long long same = __ballot(match && digit == d0);
+                    if (lane == leader)
+                        atomicAdd(&hist[wave][d0], static_cast<uint32_t>(__popcll(same)));
+                    else if (match && digit != d0)
+                        atomicAdd(&hist[wave][digit], 1u);
+                }
+            }
         }
         __syncthreads();
         if (tid < 256) {
@@ -88,21 +114,30 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
             if (above < need && need <= above + local) {
                 uint32_t cum = above;
                 int digit = lane * 4;
-                uint32_t remaining = need;
+                uint32_t remaining = need, in_bin = 0;
 #pragma unroll
                 for (int j = 3; j >= 0; --j) {
-                    if (cum + h[j] >= need) { digit = lane * 4 + j; remaining = need - cum; break; }
+                    if (cum + h[j] >= need) {
+                        digit = lane * 4 + j; remaining = need - cum; in_bin = h[j];
+                        break;
+                    }
                     cum += h[j];
                 }
                 sh_digit = static_cast<uint32_t>(digit);
                 sh_need = remaining;
+                sh_bin = in_bin;
             }
         }
         __syncthreads();
         prefix |= static_cast<uint64_t>(sh_digit) << shift;
         prefix_mask |= 0xffull << shift;
         need = sh_need;
+        const bool take_all = sh_bin == need;
         __syncthreads();
+        // Once every window that still matches the prefix is wanted, the remaining digits
+        // decide nothing: the threshold is the smallest composite with this prefix.  This is
+        // the usual case after the score digits, where a tie at the boundary is rare.
+        if (take_all) break;
     }
     const uint64_t threshold = prefix;      // the M-th largest composite itself
 
@@ -110,9 +145,19 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float *__restric
     if (tid == 0) sh_count = 0;
     for (int i = tid; i < sort_len; i += kThreads) buf[i] = 0;   // 0 sorts below every composite
     __syncthreads();
-    for (int i = tid; i < B; i += kThreads) {
-        const uint64_t c = composite(score[i], i);
-        if (c >= threshold) buf[atomicAdd(&sh_count, 1u)] = c;   // slot order is settled by the sort
+    for (int i0 = 0; i0 < B; i0 += kThreads) {
+        const int i = i0 + tid;
+        const uint64_t c = i < B ? composite(score[i], i) : 0;
+        const bool keep = i < B && c >= threshold;
+        const unsigned long long kept = __ballot(keep);           // one counter update per wave
+        if (kept) {
+            const int leader = __ffsll(static_cast<long long>(kept)) - 1;
+            uint32_t base = 0;
+            if (lane == leader) base = atomicAdd(&sh_count, static_cast<uint32_t>(__popcll(kept)));
+            base = __shfl(base, leader, 64);
+            if (keep)       // slot order is settled by the sort
+                buf[base + __popcll(kept & ((1ull << lane) - 1ull))] = c;
+        }
     }
     __syncthreads();
 

@@ -109,7 +109,10 @@ __global__ __launch_bounds__(kThreads) void group_epilogue_kernel(GroupArgs args
 //   uniform draw, the running sum kept in double and in index order (so the decision is the
 //   one a double-precision reference takes on the same fp32 scores); all-zero scores fall
 //   back to a uniform draw floor(u * W).
+constexpr int kSeqLdsScores = 8192;        // window scores of one sequence staged in LDS (32 KB)
+
 __global__ __launch_bounds__(kThreads) void sequence_windows_kernel(SequenceArgs args) {
+    __shared__ float sh_score[kSeqLdsScores];
     const int64_t n = blockIdx.x;
     const int T = args.T, K = args.K, W = T - K + 1;
     const RowRecord *rec = args.records + n * T;
@@ -119,25 +122,54 @@ __global__ __launch_bounds__(kThreads) void sequence_windows_kernel(SequenceArgs
     for (int j = threadIdx.x; j < W; j += kThreads) {
         float sum = 0.f;
         for (int t = 0; t < K; ++t) sum += rec[j + t].criticality;
-        score[j] = sum / static_cast<float>(K);
+        const float s = sum / static_cast<float>(K);
+        score[j] = s;
+        if (j < kSeqLdsScores) sh_score[j] = s;
     }
     if (!args.sampled_start) return;
     __syncthreads();                        // the scores of this sequence are all written
     if (threadIdx.x == 0) {
+        // One lane walks the scores in index order with a double running sum: first the part
+        // staged in LDS, fetched eight at a time so that the additions, not the loads, set the
+        // pace, then whatever a very long sequence left in memory.
+        const int in_lds = W < kSeqLdsScores ? W : kSeqLdsScores;
         double total = 0.0;
-        for (int j = 0; j < W; ++j) total += static_cast<double>(score[j]);
+        int j = 0;
+        for (; j + 8 <= in_lds; j += 8) {
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = sh_score[j + i];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) total += static_cast<double>(x[i]);
+        }
+        for (; j < in_lds; ++j) total += static_cast<double>(sh_score[j]);
+        for (; j < W; ++j) total += static_cast<double>(score[j]);
         const double u = static_cast<double>(args.uniforms[n]);
         int pick = W - 1;
         if (!(total > 0.0)) {
-            const int j = static_cast<int>(floor(u * static_cast<double>(W)));
-            pick = j < W - 1 ? j : W - 1;
+            const int f = static_cast<int>(floor(u * static_cast<double>(W)));
+            pick = f < W - 1 ? f : W - 1;
         } else {
             const double threshold = u * total;
             double c = 0.0;
-            for (int j = 0; j < W; ++j) {
-                c += static_cast<double>(score[j]);
-                if (c >= threshold) { pick = j; break; }
+            int first = W;                    // first index whose running sum reaches the threshold
+            for (j = 0; j + 8 <= in_lds && first == W; j += 8) {
+                float x[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) x[i] = sh_score[j + i];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    c += static_cast<double>(x[i]);
+                    first = (first == W && c >= threshold) ? j + i : first;
+                }
             }
+            if (first == W) {
+                for (; j < W; ++j) {
+                    c += static_cast<double>(j < kSeqLdsScores ? sh_score[j] : score[j]);
+                    if (c >= threshold) { first = j; break; }
+                }
+            }
+            pick = first < W ? first : W - 1;
         }
         args.sampled_start[n] = pick;
     }

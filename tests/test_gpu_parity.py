@@ -265,7 +265,8 @@ def _sequence_inputs(N, T, V, dtype, seed, sigma=0.8):
 
 @pytest.mark.parametrize("N,T,V,K,dtype", [(3, 12, 1001, 4, torch.float32), (2, 40, 4099, 10, torch.bfloat16),
                                            (5, 7, 300, 7, torch.float32), (4, 9, 515, 1, torch.bfloat16),
-                                           (1, 300, 2000, 64, torch.float32)])
+                                           (1, 300, 2000, 64, torch.float32),
+                                           (1, 8300, 64, 5, torch.float32)])
 def test_sequence_mode_matches_oracle(N, T, V, K, dtype):
     a, b, u = _sequence_inputs(N, T, V, dtype, seed=N * 1000 + T)
     out = ppow.ppow_adaw_sequence(b, a, K, u)
