@@ -66,6 +66,11 @@ def cpu_baseline(w, inputs, gpu_out, seconds):
     n = int(min(w.B, max(probe, probe * seconds / max(dt, 1e-6))))
     if n > probe:
         res, dt = run(n)
+    # single-thread rate on a small fixed subset, for a per-core figure
+    one = min(w.B, 16)
+    oracle.set_threads(1)
+    _, dt1 = run(one)
+    oracle.set_threads(res.threads)
     k_gpu = gpu_out.accepted_len[:n].cpu().numpy()
     s_gpu = gpu_out.adaw_score[:n].cpu().numpy().astype(np.float64)
     rtol = 2e-3 if w.dtype == "bf16" else 1e-4
@@ -73,7 +78,9 @@ def cpu_baseline(w, inputs, gpu_out, seconds):
                   np.all(np.abs(s_gpu - res.adaw_score) <= rtol * np.abs(res.adaw_score) + 1e-6))
     return {"value": n / dt, "unit": "windows/s", "cores": res.threads, "kind": "oracle",
             "sample": f"first {n} of {w.B} windows of the timed batch, scoring + selection, "
-                      f"{dt:.1f} s", "gpu_matches_oracle_on_sample": agrees}
+                      f"{dt:.1f} s", "single_thread_value": one / dt1,
+            "single_thread_sample": f"first {one} windows, 1 thread, {dt1:.1f} s",
+            "gpu_matches_oracle_on_sample": agrees}
 
 
 def measured_traffic(name):

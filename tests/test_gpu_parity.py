@@ -319,6 +319,32 @@ def test_second_pass_rows_longer_than_one_slice_and_many_rows_per_cluster():
         assert ppow.last_row_kernel() == "row"
 
 
+def test_calls_on_a_side_stream_and_back_to_back_calls_sharing_a_workspace():
+    """The library enqueues on the stream it is given; calls that share a workspace on one
+    stream run one after another and must not disturb each other."""
+    w = WORKLOADS["tiny_f32"].scaled(32)
+    d = generate(w, device=DEV)
+    ref = run_oracle(d, cost_ratio=w.cost_ratio, verify=w.verify, expected_accept=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    flags = ppow.PPOW_FLAG_EXPECTED_ACCEPT
+    opt = ("delta", "kl", "confidence", "accept_prob", "logp_target_tok", "logp_draft_tok",
+           "expected_accept")
+    with torch.cuda.stream(side):
+        bufs = ppow.ScoreBuffers(w.B, w.K, w.V, ppow.PPOW_F32, DEV, opt, flags)
+        halves = [bufs.window_slice(0, 16), bufs.window_slice(16, 32)]
+        for rep in range(3):                      # same workspace, alternating halves
+            for h, (lo, hi) in zip(halves, ((0, 16), (16, 32))):
+                ppow.ppow_score_windows(d["draft_logits"][lo:hi], d["target_logits"][lo:hi],
+                                        d["draft_tokens"][lo:hi], d["uniforms"][lo:hi],
+                                        cost_ratio=w.cost_ratio, flags=flags, buffers=h, stream=side)
+        sel = ppow.ppow_select_windows(bufs.adaw_score, w.M, stream=side)
+    side.synchronize()
+    compare(bufs, ref, w.dtype, w.V, True)
+    assert np.array_equal(sel.indices.cpu().numpy(),
+                          oracle.select_windows(bufs.adaw_score.cpu().numpy().astype(np.float64), w.M))
+
+
 def test_results_are_bitwise_reproducible():
     w = WORKLOADS["rejection_bf16_128k"].scaled(16)
     d = generate(w, device=DEV)
