@@ -104,9 +104,9 @@ __global__ void zero_words_kernel(uint32_t *p, int n) {
 constexpr size_t kTimingOffset = 768 * 1024;    // inside the 1 MiB scratch, past every slot
 #endif
 
-// What the closing member keeps of a row until it closes it.
+// What the closing member keeps of a row until it closes it (in LDS: it outlives the row by
+// most of the next one, and registers are what limits how much of a slice stays on chip).
 struct PendingClose {
-    bool open;
     int64_t row;
     uint32_t tag;
     const uint64_t *slot_base;
@@ -163,8 +163,8 @@ void row_cluster_kernel(ClusterArgs ca) {
     raw4 *lds_a = lds;
     raw4 *lds_b = lds + ca.slice_chunks;
 
-    PendingClose pending;
-    pending.open = false;
+    __shared__ PendingClose pending;
+    bool pending_open = false;
 #if PPOW_CLUSTER_TIMING
     long long phase_[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     long long last_ = clock64();
@@ -330,8 +330,8 @@ void row_cluster_kernel(ClusterArgs ca) {
         // min-sums were published a whole row ago, and the other members are now busy
         // reaching the exchange this member has just joined.
         PPOW_TICK(2);                                   // publish
-        if (pending.open && wave == 0) close_row<DTYPE>(ca, pending, lane);
-        pending.open = false;
+        if (pending_open && wave == 0) close_row<DTYPE>(ca, pending, lane);
+        pending_open = false;
         PPOW_TICK(3);                                   // deferred close
 
         // ---- wave 0 collects the S partials (member l on lane l) and combines them ----------
@@ -429,17 +429,19 @@ void row_cluster_kernel(ClusterArgs ca) {
         // ---- the closing member (it rotates with the epoch) finishes the row later, after it
         //      has joined the next row's exchange (or after the loop) ---------------------------
         if (closer) {
-            pending.open = true;
-            pending.row = row;
-            pending.tag = tag;
-            pending.slot_base = slot_base;
-            pending.totals = g;
-            pending.drafted = drafted;
+            pending_open = true;
+            if (tid == 0) {         // read again by wave 0 only, after the barriers in between
+                pending.row = row;
+                pending.tag = tag;
+                pending.slot_base = slot_base;
+                pending.totals = g;
+                pending.drafted = drafted;
+            }
         }
         __syncthreads();        // sh_* and the LDS slice are reused by the next row
         PPOW_TICK(6);                                   // second publish + barriers
     }
-    if (pending.open && wave == 0) close_row<DTYPE>(ca, pending, lane);
+    if (pending_open && wave == 0) close_row<DTYPE>(ca, pending, lane);
 #if PPOW_CLUSTER_TIMING
     if (tid == 0) {
         long long *out = reinterpret_cast<long long *>(reinterpret_cast<char *>(ca.status) + kTimingOffset) +
