@@ -9,8 +9,9 @@ import numpy as np
 import pytest
 import torch
 
+import oracle
 import paper_2605_14978_amd as ppow
-from workloads import WORKLOADS, generate
+from workloads import WORKLOADS, generate, generate_sequences
 
 from parity import check_selection, compare, run_oracle
 
@@ -85,4 +86,26 @@ def test_full_size_workload(name):
         torch.cuda.empty_cache()
     _check_properties(w, out)
     idx = check_selection(out.adaw_score, w.M)          # global top-M over every chunk
+    assert len(set(idx.tolist())) == w.M
+
+
+def test_full_size_sequence_mode():
+    """Sequence-mode ADAW at the benchmark's size: two sampled sequences against the oracle,
+    the sampler and the selection exactly on the GPU's own scores."""
+    from parity import RTOL, assert_close
+    w = WORKLOADS["sequence_bf16_128k"]
+    N, T, K = w.B, w.seq_len, w.K
+    d = generate_sequences(w, device=DEV)
+    out = ppow.ppow_adaw_sequence(d["draft_logits"], d["target_logits"], K, d["uniforms"])
+    torch.cuda.synchronize()
+    for n in (3, N - 1):
+        print(f"sequence {n}", flush=True)
+        v_ref, s_ref = oracle.adaw_sequence(d["draft_logits"][n:n + 1].cpu(), d["target_logits"][n:n + 1].cpu(), K)
+        assert_close("criticality", out.criticality[n].cpu(), v_ref, RTOL[w.dtype])
+        assert_close("window_score", out.window_score[n].cpu(), s_ref, RTOL[w.dtype])
+    s_gpu = out.window_score.cpu().numpy().astype(np.float64)
+    picks = oracle.sample_starts(s_gpu, d["uniforms"].cpu().numpy().astype(np.float64))
+    assert np.array_equal(out.sampled_start.cpu().numpy(), picks)
+    assert s_gpu.min() >= 0 and np.all(np.isfinite(s_gpu))
+    idx = check_selection(out.window_score.view(-1), w.M)
     assert len(set(idx.tolist())) == w.M

@@ -345,6 +345,42 @@ def test_calls_on_a_side_stream_and_back_to_back_calls_sharing_a_workspace():
                           oracle.select_windows(bufs.adaw_score.cpu().numpy().astype(np.float64), w.M))
 
 
+def test_scoring_and_selection_replay_from_a_hip_graph():
+    """The single-pass path allocates nothing and records no memset node, so it can be captured
+    once and replayed; every replay must reproduce the eager result bit for bit, with eager work
+    and synchronisations in between."""
+    w = WORKLOADS["greedy_bf16_32k"].scaled(64)
+    d = generate(w, device=DEV)
+    bufs = ppow.ScoreBuffers(w.B, w.K, w.V, ppow.PPOW_BF16, DEV, ("delta", "kl"))
+    sel = ppow.SelectBuffers(w.B, w.M, DEV)
+
+    def step():
+        ppow.ppow_score_windows(d["draft_logits"], d["target_logits"], d["draft_tokens"], None,
+                                cost_ratio=w.cost_ratio, verify=ppow.PPOW_VERIFY_GREEDY, buffers=bufs)
+        ppow.ppow_select_windows(bufs.adaw_score, w.M, buffers=sel)
+
+    step()
+    torch.cuda.synchronize()
+    eager = {n: getattr(bufs, n).clone() for n in ("accepted_len", "r_speedup", "adaw_score", "kl")}
+    eager_idx = sel.indices.clone()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for replay in range(3):
+        for t in (bufs.accepted_len, bufs.r_speedup, bufs.adaw_score, bufs.kl, sel.indices):
+            t.zero_()                                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, ref in eager.items():
+            assert torch.equal(getattr(bufs, n), ref), (replay, n)
+        assert torch.equal(sel.indices, eager_idx), replay
+
+
 def test_results_are_bitwise_reproducible():
     w = WORKLOADS["rejection_bf16_128k"].scaled(16)
     d = generate(w, device=DEV)
