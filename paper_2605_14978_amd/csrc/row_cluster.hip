@@ -44,7 +44,8 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kRegChunks = PPOW_CLUSTER_REG_CHUNKS;
 constexpr int kMaxMembers = 64;                // one lane of a wavefront per member
 constexpr int kSlotWords = 16;                 // 64-bit words per member and parity (10 used)
-constexpr unsigned kMaxSpins = 1u << 17;       // a fraction of a second: far beyond any legitimate wait
+constexpr unsigned kMaxSpins = 1u << 24;       // many seconds: members may be kept off the GPU for a
+                                               // while by other streams' kernels, never this long
 
 // scratch layout (bytes): [0,4) status | [256, ...) slots
 constexpr size_t kSlotOffset = 256;

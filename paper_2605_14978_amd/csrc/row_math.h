@@ -159,25 +159,52 @@ __device__ __forceinline__ float min_prob_sum(const float (&a)[VEC], const float
     return acc;
 }
 
+// Wave-wide reductions without LDS traffic: four data-parallel-primitive steps reduce each row
+// of 16 lanes (lane i pairs with i^1, i^2, then with the mirrored lane of its half row and of
+// its row, which by then hold the partner quad's / half row's value), and the four row results
+// are read out as scalars.  Every lane returns the same bits; the order of the additions is
+// fixed, so results repeat from run to run.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+        0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true);
+}
+constexpr int kDppXor1 = 0xB1;          // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // row_half_mirror
+constexpr int kDppMirror = 0x140;       // row_mirror
+
+__device__ __forceinline__ float row_lane(float x, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
+
 __device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
-    return x;
+    x = fmaxf(x, dpp_move<kDppXor1>(x));
+    x = fmaxf(x, dpp_move<kDppXor2>(x));
+    x = fmaxf(x, dpp_move<kDppHalfMirror>(x));
+    x = fmaxf(x, dpp_move<kDppMirror>(x));
+    return fmaxf(fmaxf(row_lane(x, 0), row_lane(x, 16)), fmaxf(row_lane(x, 32), row_lane(x, 48)));
 }
 
 __device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
-    return x;
+    x += dpp_move<kDppXor1>(x);
+    x += dpp_move<kDppXor2>(x);
+    x += dpp_move<kDppHalfMirror>(x);
+    x += dpp_move<kDppMirror>(x);
+    return (row_lane(x, 0) + row_lane(x, 16)) + (row_lane(x, 32) + row_lane(x, 48));
 }
 
 __device__ __forceinline__ int wave_min(int x) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const int other = __shfl_xor(x, off, 64);
-        x = other < x ? other : x;
-    }
-    return x;
+    x = min(x, dpp_move<kDppXor1>(x));
+    x = min(x, dpp_move<kDppXor2>(x));
+    x = min(x, dpp_move<kDppHalfMirror>(x));
+    x = min(x, dpp_move<kDppMirror>(x));
+    return min(min(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+               min(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
 }
 
 // Sums of one row pair relative to the references ref_a / ref_b, plus the exact target maximum.

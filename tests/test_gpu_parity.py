@@ -317,6 +317,13 @@ def test_second_pass_rows_longer_than_one_slice_and_many_rows_per_cluster():
         assert ppow.last_row_kernel() == "cluster"          # the LDS-resident path really ran
         _check(d, V, M=20)
         assert ppow.last_row_kernel() == "row"
+    # greedy verification together with the second pass
+    d = _random_inputs(40, 5, 9001, torch.bfloat16, seed=77, greedy=True)
+    d["draft_tokens"] = torch.where(torch.rand(40, 5, device=DEV) < 0.7,
+                                    d["target_logits"].float().argmax(-1).to(torch.int32),
+                                    d["draft_tokens"]).contiguous()
+    gpu, ref = _check(d, 9001, verify="greedy", expected_accept=True)
+    assert 0 < ref.accepted_len.mean() < 5
 
 
 def test_calls_on_a_side_stream_and_back_to_back_calls_sharing_a_workspace():
