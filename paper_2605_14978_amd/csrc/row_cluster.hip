@@ -43,12 +43,14 @@ constexpr int kThreads = PPOW_CLUSTER_THREADS;
 constexpr int kWaves = kThreads / 64;
 constexpr int kRegChunks = PPOW_CLUSTER_REG_CHUNKS;
 constexpr int kMaxMembers = 64;                // one lane of a wavefront per member
-constexpr int kSlotWords = 16;                 // 64-bit words per member and parity (10 used)
+constexpr int kExchanged = 10;                 // words a member publishes per row
 constexpr unsigned kMaxSpins = 1u << 24;       // many seconds: members may be kept off the GPU for a
                                                // while by other streams' kernels, never this long
 
 // scratch layout (bytes): [0,4) status | [256, ...) slots
 constexpr size_t kSlotOffset = 256;
+constexpr size_t kSlotLimit = 768 * 1024;      // slots end here (phase timings of a tuning build follow)
+static_assert(kSlotLimit + 256 * 1024 <= kClusterScratchBytes, "scratch layout");
 constexpr int kMaxClusters = 4096;
 
 struct ClusterArgs {
@@ -58,7 +60,10 @@ struct ClusterArgs {
     int32_t clusters;
     int32_t slice_chunks;   // LDS part of a slice per row side, in 128-bit chunks
     uint32_t *status;
-    uint64_t *slots;        // [clusters][2][S][kSlotWords]
+    uint64_t *slots;        // [clusters][2][kExchanged][stride]: word i of all members side by
+                            // side, so the wavefront that collects them (member l on lane l)
+                            // reads each word of the whole cluster with one coalesced request
+    int32_t stride;         // S rounded up to a multiple of 8 (64 bytes)
 };
 
 // 128-bit load from global memory straight into LDS: lane i of the wave writes 16 bytes at
@@ -102,7 +107,7 @@ __global__ void zero_words_kernel(uint32_t *p, int n) {
 #define PPOW_TICK(i) do { } while (0)
 #endif
 #if PPOW_CLUSTER_TIMING
-constexpr size_t kTimingOffset = 768 * 1024;    // inside the 1 MiB scratch, past every slot
+constexpr size_t kTimingOffset = kSlotLimit;
 #endif
 
 // What the closing member keeps of a row until it closes it (in LDS: it outlives the row by
@@ -119,7 +124,7 @@ struct PendingClose {
 template <int DTYPE>
 __device__ __forceinline__ void close_row(const ClusterArgs &ca, const PendingClose &p, int lane) {
     const bool has = lane < ca.members;
-    const uint64_t *word = p.slot_base + (has ? lane : 0) * kSlotWords + 9;
+    const uint64_t *word = p.slot_base + 9 * ca.stride + (has ? lane : 0);
     uint64_t w = 0;
     unsigned spins = 0;
     for (;;) {
@@ -146,6 +151,7 @@ void row_cluster_kernel(ClusterArgs ca) {
     constexpr int kRegSpan = kRegChunks * kThreads;       // chunks of a slice kept in registers
 
     extern __shared__ raw4 lds[];
+    __shared__ float sh_m[kWaves][3];
     __shared__ float sh_f[kWaves][6];
     __shared__ int sh_i[kWaves];
     __shared__ int sh_abort;
@@ -251,16 +257,16 @@ void row_cluster_kernel(ClusterArgs ca) {
         t.ref_a = wave_max(s.rho_a);
         t.ref_b = wave_max(s.rho_b);
         t.row_max = wave_max(fmaxf(s.m_a, rag_v));
-        if (lane == 0) { sh_f[wave][0] = t.ref_a; sh_f[wave][1] = t.ref_b; sh_f[wave][2] = t.row_max; }
+        if (lane == 0) { sh_m[wave][0] = t.ref_a; sh_m[wave][1] = t.ref_b; sh_m[wave][2] = t.row_max; }
         __syncthreads();
-        t.ref_a = sh_f[0][0]; t.ref_b = sh_f[0][1]; t.row_max = sh_f[0][2];
+        t.ref_a = sh_m[0][0]; t.ref_b = sh_m[0][1]; t.row_max = sh_m[0][2];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) {
-            t.ref_a = fmaxf(t.ref_a, sh_f[w][0]);
-            t.ref_b = fmaxf(t.ref_b, sh_f[w][1]);
-            t.row_max = fmaxf(t.row_max, sh_f[w][2]);
+            t.ref_a = fmaxf(t.ref_a, sh_m[w][0]);
+            t.ref_b = fmaxf(t.ref_b, sh_m[w][1]);
+            t.row_max = fmaxf(t.row_max, sh_m[w][2]);
         }
-        __syncthreads();
+        // (the sums below go to sh_f, not over sh_m: no barrier needed before they are written)
 
         // First index of the slice maximum among this lane's own chunks (registers, then LDS):
         // a lane that holds the maximum scans its chunks in index order.
@@ -303,28 +309,27 @@ void row_cluster_kernel(ClusterArgs ca) {
         // ---- publish the slice's partial sums ------------------------------------------------
         const uint32_t tag = epoch + 1u;
         uint64_t *slot_base = ca.slots + (static_cast<size_t>(cluster) * 2 + (epoch & 1u)) *
-                                             members * kSlotWords;
-        uint64_t *my_slot = slot_base + member * kSlotWords;
-        if (tid == 0) {
-            float z_a = sh_f[0][0], s1 = sh_f[0][1], s2 = sh_f[0][2], z_b = sh_f[0][3];
-            float s2r = sh_f[0][4];
-            int best = sh_i[0];
+                                             kExchanged * ca.stride;
+        uint64_t *my_slot = slot_base + member;
+        if (tid < 9) {
+            // lane i publishes word i: the two references, the five sums (added over the waves
+            // in wave order), the slice maximum and its first index; an empty slice publishes
+            // the neutral element (references at -inf)
+            uint32_t bits;
+            if (tid >= 2 && tid <= 6) {
+                float v = sh_f[0][tid - 2];
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w) {
-                z_a += sh_f[w][0]; s1 += sh_f[w][1]; s2 += sh_f[w][2]; z_b += sh_f[w][3];
-                s2r += sh_f[w][4];
-                best = sh_i[w] < best ? sh_i[w] : best;
+                for (int w = 1; w < kWaves; ++w) v += sh_f[w][tid - 2];
+                bits = __builtin_bit_cast(uint32_t, v);
+            } else if (tid == 8) {
+                int best = sh_i[0];
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) best = sh_i[w] < best ? sh_i[w] : best;
+                bits = static_cast<uint32_t>(best);
+            } else {
+                bits = __builtin_bit_cast(uint32_t, tid == 0 ? t.ref_a : tid == 1 ? t.ref_b : t.row_max);
             }
-            // an empty slice publishes the neutral element (references at -inf)
-            publish(my_slot + 0, tag, t.ref_a);
-            publish(my_slot + 1, tag, t.ref_b);
-            publish(my_slot + 2, tag, z_a);
-            publish(my_slot + 3, tag, s1);
-            publish(my_slot + 4, tag, s2);
-            publish(my_slot + 5, tag, z_b);
-            publish(my_slot + 6, tag, s2r);
-            publish(my_slot + 7, tag, t.row_max);
-            publish(my_slot + 8, tag, static_cast<uint32_t>(best));
+            publish(my_slot + tid * ca.stride, tag, bits);
         }
 
         // A row this member still has to close is closed here, off the critical path: its
@@ -338,7 +343,7 @@ void row_cluster_kernel(ClusterArgs ca) {
         // ---- wave 0 collects the S partials (member l on lane l) and combines them ----------
         if (wave == 0) {
             const bool has = lane < members;
-            const uint64_t *slot = slot_base + (has ? lane : 0) * kSlotWords;
+            const uint64_t *slot = slot_base + (has ? lane : 0);
             uint64_t w[9];
             unsigned spins = 0;
             int abort = 0;
@@ -346,7 +351,7 @@ void row_cluster_kernel(ClusterArgs ca) {
                 bool ok = true;
 #pragma unroll
                 for (int i = 0; i < 9; ++i) {
-                    w[i] = observe(slot + i);
+                    w[i] = observe(slot + i * ca.stride);
                     ok = ok && tagged(w[i], tag);
                 }
                 if (__all(ok || !has)) break;
@@ -424,7 +429,7 @@ void row_cluster_kernel(ClusterArgs ca) {
             float part = sh_f[0][5];
 #pragma unroll
             for (int w = 1; w < kWaves; ++w) part += sh_f[w][5];
-            publish(my_slot + 9, tag, part);
+            publish(my_slot + 9 * ca.stride, tag, part);
         }
 
         // ---- the closing member (it rotates with the epoch) finishes the row later, after it
@@ -494,6 +499,10 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
     int64_t clusters = static_cast<int64_t>(per_cu) * cus / ca.members;
     if (clusters > ca.rows) clusters = ca.rows;
     if (clusters > kMaxClusters) clusters = kMaxClusters;
+    // both parities of every cluster's exchange words have to fit the scratch
+    const size_t per_cluster = static_cast<size_t>(2) * kExchanged * ca.stride * 8;
+    const int64_t fit = static_cast<int64_t>((kSlotLimit - kSlotOffset) / per_cluster);
+    if (clusters > fit) clusters = fit;
     if (clusters < 1) return hipSuccess;
     ca.clusters = static_cast<int32_t>(clusters);
 
@@ -540,14 +549,12 @@ hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, 
     ca.row = args;
     ca.rows = rows;
     ca.members = static_cast<int32_t>(members);
+    ca.stride = static_cast<int32_t>((members + 7) & ~static_cast<int64_t>(7));
     ca.clusters = 0;
     ca.slice_chunks = static_cast<int32_t>(in_lds);
     char *base = static_cast<char *>(scratch);
     ca.status = reinterpret_cast<uint32_t *>(base);
     ca.slots = reinterpret_cast<uint64_t *>(base + kSlotOffset);
-    // slots needed: clusters * 2 * members * 128 B <= (workgroups per CU * cus) * 256 B
-    if (static_cast<size_t>(dev.cus) * 8 * 2 * kSlotWords * 8 + kSlotOffset > kClusterScratchBytes)
-        return hipSuccess;
 
     if (dtype == PPOW_BF16) {
         if (args.want_policy_terms) return launch_variant<PPOW_BF16, true>(ca, lds_bytes, dev.cus, stream, launched);
