@@ -149,6 +149,7 @@ void row_cluster_kernel(ClusterArgs ca) {
     using elem = typename S::elem;
     constexpr int VEC = S::VEC;
     constexpr int kRegSpan = kRegChunks * kThreads;       // chunks of a slice kept in registers
+    constexpr bool KEEP = DTYPE == PPOW_F32;              // 4 fp32 per chunk: room for the exponentials
 
     extern __shared__ raw4 lds[];
     __shared__ float sh_m[kWaves][3];
@@ -221,6 +222,38 @@ void row_cluster_kernel(ClusterArgs ca) {
         }
         LaneState s;
         s.reset();
+        // fp32 rows: the raw logits are not needed after this pass, so the two exponentials of
+        // every pair take their place in the registers / LDS and pass 2 only rescales them
+        // (the position of the lane's maximum is tracked to the element instead of re-scanned).
+        // If a lane's reference moves (rare), what it has kept so far is rescaled to the new one.
+        int first_elem = -1;
+        auto rescale_kept = [&](int regs_upto, int lds_upto, float fa, float fb) {
+#pragma unroll
+            for (int k = 0; k < kRegChunks; ++k) {
+                if (k < regs_upto && tid + k * kThreads < n) {
+                    float ea[VEC], eb[VEC];
+                    S::unpack(ka[k], ea);
+                    S::unpack(kb[k], eb);
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) { ea[j] *= fa; eb[j] *= fb; }
+                    if constexpr (KEEP) { ka[k] = S::pack(ea); kb[k] = S::pack(eb); }
+                }
+            }
+            for (int c = tid + kRegSpan; c < lds_upto; c += kThreads) {
+                float ea[VEC], eb[VEC];
+                S::unpack(lds_a[c - kRegSpan], ea);
+                S::unpack(lds_b[c - kRegSpan], eb);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) { ea[j] *= fa; eb[j] *= fb; }
+                if constexpr (KEEP) { lds_a[c - kRegSpan] = S::pack(ea); lds_b[c - kRegSpan] = S::pack(eb); }
+            }
+        };
+        auto moved = [&](float ra, float rb, float &fa, float &fb) {
+            if (s.rho_a == ra && s.rho_b == rb) return false;
+            fa = fast_exp2(ra - s.rho_a);          // ra = -inf (nothing kept yet) gives 0: harmless
+            fb = fast_exp2(rb - s.rho_b);
+            return true;
+        };
 #pragma unroll
         for (int k = 0; k < kRegChunks; ++k) {
             const int cr = tid + k * kThreads;
@@ -228,7 +261,16 @@ void row_cluster_kernel(ClusterArgs ca) {
                 float a[VEC], b[VEC];
                 S::unpack(ka[k], a);
                 S::unpack(kb[k], b);
-                fold_chunk<VEC, REV>(s, a, b, cr);
+                if constexpr (KEEP) {
+                    const float ra = s.rho_a, rb = s.rho_b;
+                    float ea[VEC], eb[VEC], fa, fb;
+                    fold_chunk_keep<VEC, REV>(s, a, b, cr, first_elem, ea, eb);
+                    if (k > 0 && moved(ra, rb, fa, fb)) rescale_kept(k, 0, fa, fb);
+                    ka[k] = S::pack(ea);
+                    kb[k] = S::pack(eb);
+                } else {
+                    fold_chunk<VEC, REV>(s, a, b, cr);
+                }
             }
         }
         __builtin_amdgcn_s_waitcnt(0);              // the direct loads have landed in LDS
@@ -236,7 +278,16 @@ void row_cluster_kernel(ClusterArgs ca) {
             float a[VEC], b[VEC];
             S::unpack(lds_a[c - kRegSpan], a);
             S::unpack(lds_b[c - kRegSpan], b);
-            fold_chunk<VEC, REV>(s, a, b, c);
+            if constexpr (KEEP) {
+                const float ra = s.rho_a, rb = s.rho_b;
+                float ea[VEC], eb[VEC], fa, fb;
+                fold_chunk_keep<VEC, REV>(s, a, b, c, first_elem, ea, eb);
+                if (moved(ra, rb, fa, fb)) rescale_kept(kRegChunks, c, fa, fb);
+                lds_a[c - kRegSpan] = S::pack(ea);
+                lds_b[c - kRegSpan] = S::pack(eb);
+            } else {
+                fold_chunk<VEC, REV>(s, a, b, c);
+            }
         }
 
         PPOW_TICK(0);                                   // load + fold
@@ -248,8 +299,13 @@ void row_cluster_kernel(ClusterArgs ca) {
             rag_i = (tid < head) ? tid : tail_begin + (tid - head);
             const float a1[1] = {S::load1(row_a + rag_i)};
             const float b1[1] = {S::load1(row_b + rag_i)};
+            const float ra = s.rho_a, rb = s.rho_b;
             fold<1, REV>(s, a1, b1, a1[0], b1[0]);
             rag_v = a1[0];
+            if constexpr (KEEP) {
+                float fa, fb;
+                if (moved(ra, rb, fa, fb)) rescale_kept(kRegChunks, n, fa, fb);
+            }
         }
 
         // ---- workgroup combine of the slice ------------------------------------------------
@@ -268,28 +324,32 @@ void row_cluster_kernel(ClusterArgs ca) {
         }
         // (the sums below go to sh_f, not over sh_m: no barrier needed before they are written)
 
-        // First index of the slice maximum among this lane's own chunks (registers, then LDS):
-        // a lane that holds the maximum scans its chunks in index order.
+        // First index of the slice maximum: a lane that holds it knows the element (fp32) or
+        // scans its own chunks (registers, then LDS) in index order (bf16).
         int arg_i = (rag_v == t.row_max) ? rag_i : INT_MAX;
         if (s.m_a == t.row_max && s.best >= 0) {
             int found = INT_MAX;
+            if constexpr (KEEP) {
+                found = head + c0 * VEC + first_elem;
+            } else {
 #pragma unroll
-            for (int k = kRegChunks - 1; k >= 0; --k) {
-                const int cr = tid + k * kThreads;
-                if (cr < n) {
+                for (int k = kRegChunks - 1; k >= 0; --k) {
+                    const int cr = tid + k * kThreads;
+                    if (cr < n) {
+                        float a[VEC];
+                        S::unpack(ka[k], a);
+#pragma unroll
+                        for (int j = VEC - 1; j >= 0; --j)
+                            found = (a[j] == t.row_max) ? head + (c0 + cr) * VEC + j : found;
+                    }
+                }
+                if (found == INT_MAX) {               // not in the register part: the LDS chunk
                     float a[VEC];
-                    S::unpack(ka[k], a);
+                    S::unpack(lds_a[s.best - kRegSpan], a);
 #pragma unroll
                     for (int j = VEC - 1; j >= 0; --j)
-                        found = (a[j] == t.row_max) ? head + (c0 + cr) * VEC + j : found;
+                        found = (a[j] == t.row_max) ? head + (c0 + s.best) * VEC + j : found;
                 }
-            }
-            if (found == INT_MAX) {                   // not in the register part: the LDS chunk
-                float a[VEC];
-                S::unpack(lds_a[s.best - kRegSpan], a);
-#pragma unroll
-                for (int j = VEC - 1; j >= 0; --j)
-                    found = (a[j] == t.row_max) ? head + (c0 + s.best) * VEC + j : found;
             }
             arg_i = found < arg_i ? found : arg_i;
         }
@@ -401,20 +461,25 @@ void row_cluster_kernel(ClusterArgs ca) {
         const float lam_a = g.ref_a + fast_log2(g.z_a);
         const float lam_b = g.ref_b + fast_log2(g.z_b);
         float acc = 0.f;
+        // kept exponentials are relative to this lane's references: one scale per side
+        const float keep_a = (KEEP && s.rho_a != PPOW_NEG_INF) ? fast_exp2(s.rho_a - lam_a) : 0.f;
+        const float keep_b = (KEEP && s.rho_b != PPOW_NEG_INF) ? fast_exp2(s.rho_b - lam_b) : 0.f;
 #pragma unroll
         for (int k = 0; k < kRegChunks; ++k) {
             if (tid + k * kThreads < n) {
                 float a[VEC], b[VEC];
                 S::unpack(ka[k], a);
                 S::unpack(kb[k], b);
-                acc += min_prob_sum<VEC>(a, b, lam_a, lam_b);
+                acc += KEEP ? min_prob_sum_kept<VEC>(a, b, keep_a, keep_b)
+                            : min_prob_sum<VEC>(a, b, lam_a, lam_b);
             }
         }
         for (int cc = tid + kRegSpan; cc < n; cc += kThreads) {
             float a[VEC], b[VEC];
             S::unpack(lds_a[cc - kRegSpan], a);
             S::unpack(lds_b[cc - kRegSpan], b);
-            acc += min_prob_sum<VEC>(a, b, lam_a, lam_b);
+            acc += KEEP ? min_prob_sum_kept<VEC>(a, b, keep_a, keep_b)
+                        : min_prob_sum<VEC>(a, b, lam_a, lam_b);
         }
         if (tid < ragged) {
             const float a1[1] = {S::load1(row_a + rag_i)};

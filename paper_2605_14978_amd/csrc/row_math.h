@@ -58,6 +58,12 @@ struct Storage<PPOW_F32> {
         x[0] = as_float(r.x); x[1] = as_float(r.y); x[2] = as_float(r.z); x[3] = as_float(r.w);
     }
     static __device__ __forceinline__ float load1(const elem *p) { return *p; }
+    static __device__ __forceinline__ raw4 pack(const float (&x)[VEC]) {
+        raw4 r;
+        r.x = __builtin_bit_cast(uint32_t, x[0]); r.y = __builtin_bit_cast(uint32_t, x[1]);
+        r.z = __builtin_bit_cast(uint32_t, x[2]); r.w = __builtin_bit_cast(uint32_t, x[3]);
+        return r;
+    }
 };
 
 template <>
@@ -109,10 +115,12 @@ __device__ __forceinline__ void rebase_draft(LaneState &s, float new_rho) {
     s.rho_b = new_rho;
 }
 
-// Fold VEC element pairs into the running sums (no argmax bookkeeping).
-template <int VEC, bool REV>
-__device__ __forceinline__ void fold(LaneState &s, const float (&a)[VEC], const float (&b)[VEC],
-                                     float cma, float cmb) {
+// Fold VEC element pairs into the running sums (no argmax bookkeeping).  With KEEP the two
+// exponentials of every pair, 2^(a*log2e - rho_a) and 2^(b*log2e - rho_b) relative to the
+// references as they stand after this call, are handed back for a later pass.
+template <int VEC, bool REV, bool KEEP>
+__device__ __forceinline__ void fold_impl(LaneState &s, const float (&a)[VEC], const float (&b)[VEC],
+                                          float cma, float cmb, float *ea, float *eb_out) {
     const float ta_max = fmaf(cma, kLog2e, -s.rho_a);
     const float tb_max = fmaf(cmb, kLog2e, -s.rho_b);
     if (fmaxf(ta_max, tb_max) > kRescaleGap) {      // rare: the reference lags too far behind
@@ -131,7 +139,14 @@ __device__ __forceinline__ void fold(LaneState &s, const float (&a)[VEC], const 
         const float eb = fast_exp2(tb);
         s.z_b += eb;
         if (REV) s.s2r = fmaf(eb, -d, s.s2r);
+        if (KEEP) { ea[j] = e; eb_out[j] = eb; }
     }
+}
+
+template <int VEC, bool REV>
+__device__ __forceinline__ void fold(LaneState &s, const float (&a)[VEC], const float (&b)[VEC],
+                                     float cma, float cmb) {
+    fold_impl<VEC, REV, false>(s, a, b, cma, cmb, nullptr, nullptr);
 }
 
 template <int VEC, bool REV>
@@ -146,6 +161,39 @@ __device__ __forceinline__ void fold_chunk(LaneState &s, const float (&a)[VEC],
     s.best = (cma > s.m_a) ? chunk : s.best;       // strict: the first chunk keeps a tie
     s.m_a = fmaxf(s.m_a, cma);
     fold<VEC, REV>(s, a, b, cma, cmb);
+}
+
+// As fold_chunk, but the raw logits will not be looked at again: the exponentials are kept in
+// their place (ea, eb), and the position of the lane's maximum is tracked to the element
+// (first_elem = chunk * VEC + first j of the chunk that reaches the chunk maximum).
+template <int VEC, bool REV>
+__device__ __forceinline__ void fold_chunk_keep(LaneState &s, const float (&a)[VEC],
+                                                const float (&b)[VEC], int chunk, int &first_elem,
+                                                float (&ea)[VEC], float (&eb)[VEC]) {
+    float cma = a[0], cmb = b[0];
+#pragma unroll
+    for (int j = 1; j < VEC; ++j) {
+        cma = fmaxf(cma, a[j]);
+        cmb = fmaxf(cmb, b[j]);
+    }
+    int jf = VEC - 1;
+#pragma unroll
+    for (int j = VEC - 2; j >= 0; --j) jf = (a[j] == cma) ? j : jf;
+    const bool better = cma > s.m_a;                // strict: the first chunk keeps a tie
+    s.best = better ? chunk : s.best;
+    first_elem = better ? chunk * VEC + jf : first_elem;
+    s.m_a = fmaxf(s.m_a, cma);
+    fold_impl<VEC, REV, true>(s, a, b, cma, cmb, ea, eb);
+}
+
+// Pass-2 contribution of VEC pairs from kept exponentials: scale_a = 2^(rho_a - lam_a) etc.
+template <int VEC>
+__device__ __forceinline__ float min_prob_sum_kept(const float (&ea)[VEC], const float (&eb)[VEC],
+                                                   float scale_a, float scale_b) {
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc += fminf(ea[j] * scale_a, eb[j] * scale_b);
+    return acc;
 }
 
 // sum_y min(P(y), Q(y)) contribution of VEC pairs; lam = log2-domain log-sum-exp

@@ -164,6 +164,25 @@ def test_reference_rescaling_on_monotone_and_wide_range_rows(dtype):
     _check(d, V)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_second_pass_on_rows_whose_reference_keeps_moving(dtype):
+    """The on-chip second pass of fp32 rows rescales exponentials it kept from the first pass;
+    a ramp along the vocabulary moves every lane's reference at every chunk, in the register
+    part, in the LDS part and at the ragged tail (V = 18001: rows are not 16-byte aligned)."""
+    B, K, V = 3, 2, 18001
+    ramp = torch.linspace(-300.0, 300.0, V)
+    a = torch.stack([ramp, ramp.flip(0), ramp * 0.05])
+    a = a[:, None, :].repeat(1, K, 1).contiguous()
+    g = torch.Generator().manual_seed(11)
+    b = a * 0.97 + torch.randn(B, K, V, generator=g)
+    tok = a.argmax(-1).to(torch.int32)
+    tok[:, 1] = (tok[:, 1] + 5) % V
+    d = _to_dev({"target_logits": a.to(dtype), "draft_logits": b.to(dtype), "draft_tokens": tok,
+                 "uniforms": torch.full((B, K), 0.5)})
+    _check(d, V, expected_accept=True)
+    assert ppow.last_row_kernel() == "cluster"
+
+
 def test_uniform_target_has_zero_confidence():
     V = 2048
     a = torch.full((2, 2, V), 1.5)
