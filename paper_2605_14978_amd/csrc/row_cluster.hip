@@ -291,6 +291,10 @@ void row_cluster_kernel(ClusterArgs ca) {
         }
 
         PPOW_TICK(0);                                   // load + fold
+        // From here to the hand-over of the row totals the workgroup does little arithmetic but
+        // sits on the critical path of its whole cluster (combine, publish, collect): its waves
+        // go ahead of the other workgroup's bulk arithmetic on this CU.
+        __builtin_amdgcn_s_setprio(1);
         // ragged ends of the row belong to member 0
         const int ragged = (member == 0) ? head + (V - tail_begin) : 0;
         float rag_v = PPOW_NEG_INF;
@@ -452,6 +456,7 @@ void row_cluster_kernel(ClusterArgs ca) {
         }
         PPOW_TICK(4);                                   // poll + combine of the partials
         __syncthreads();
+        __builtin_amdgcn_s_setprio(0);
         if (sh_abort) return;                              // uniform: the whole workgroup leaves
         RowTotals g;
         g.ref_a = sh_g[0]; g.ref_b = sh_g[1]; g.z_a = sh_g[2]; g.s1 = sh_g[3]; g.s2 = sh_g[4];
