@@ -146,6 +146,29 @@ def test_argmax_ties_take_the_lowest_index():
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_argmax_ties_in_the_second_pass_kernel(dtype):
+    """Equal maxima in different lanes, register / LDS chunks, members of a cluster and in the
+    ragged tail: the first index wins on the path that keeps the row on chip as well."""
+    V = 60001                               # fp32: two members; rows are not 16-byte aligned
+    a = torch.zeros(4, 2, V)
+    a[0, 0, [12345, 12346, 50000]] = 5.0    # inside one chunk, and in the other member
+    a[0, 1, [40000, 59999, 60000]] = 5.0    # LDS part of member 0 / member 1, and the tail
+    a[1, 0, [0, 1, 2, 3]] = 5.0             # the head, before the first aligned chunk
+    a[1, 1, [30001, 30000]] = 5.0           # around the member boundary
+    a[2, :, 2048 * 9 + 5] = 5.0
+    a[3, :, V - 1] = 5.0
+    b = a + 0.1 * torch.randn(a.shape, generator=torch.Generator().manual_seed(4))
+    first = torch.tensor([[12345, 40000], [0, 30000], [2048 * 9 + 5] * 2, [V - 1, V - 1]], dtype=torch.int32)
+    later = torch.tensor([[12346, 59999], [1, 30001], [2048 * 9 + 5] * 2, [V - 1, V - 1]], dtype=torch.int32)
+    for tok, expect in ((first, [2, 2, 2, 2]), (later, [0, 0, 2, 2])):
+        d = _to_dev({"target_logits": a.to(dtype), "draft_logits": b.to(dtype), "draft_tokens": tok,
+                     "uniforms": None})
+        gpu, ref = _check(d, V, verify="greedy", expected_accept=True)
+        assert ppow.last_row_kernel() == "cluster"
+        assert gpu.accepted_len.cpu().tolist() == expect
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_reference_rescaling_on_monotone_and_wide_range_rows(dtype):
     """Rows whose maximum keeps growing along the vocabulary force the running
     reference to be rebased many times; very negative logits must vanish cleanly."""
