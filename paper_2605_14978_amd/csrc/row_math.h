@@ -196,14 +196,16 @@ __device__ __forceinline__ float min_prob_sum_kept(const float (&ea)[VEC], const
     return acc;
 }
 
-// sum_y min(P(y), Q(y)) contribution of VEC pairs; lam = log2-domain log-sum-exp
+// sum_y min(P(y), Q(y)) contribution of VEC pairs; lam = log2-domain log-sum-exp.  The
+// exponential is monotone, so the smaller probability is the exponential of the smaller
+// exponent: one v_exp_f32 per pair instead of two.
 template <int VEC>
 __device__ __forceinline__ float min_prob_sum(const float (&a)[VEC], const float (&b)[VEC],
                                               float lam_a, float lam_b) {
     float acc = 0.f;
 #pragma unroll
     for (int j = 0; j < VEC; ++j)
-        acc += fminf(fast_exp2(fmaf(a[j], kLog2e, -lam_a)), fast_exp2(fmaf(b[j], kLog2e, -lam_b)));
+        acc += fast_exp2(fminf(fmaf(a[j], kLog2e, -lam_a), fmaf(b[j], kLog2e, -lam_b)));
     return acc;
 }
 
