@@ -111,8 +111,14 @@ size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype
  *                                storage, base pointers 16-byte aligned.  Logits
  *                                must be finite.  P_t = softmax(target row),
  *                                Q_t = softmax(draft row), temperature 1.
- *   draft_tokens                 [B, K] int32, 0 <= token < V (precondition, not
- *                                checked on the device)
+ *   draft_tokens                 [B, K] int32, 0 <= token < V.  The host cannot
+ *                                see them, so the device checks: a token outside
+ *                                the range is never used as an address; its
+ *                                window gets accepted_len = -1, r_speedup = 0 and
+ *                                r_proximity = 0 (adaw_score, kl, confidence and
+ *                                expected_accept do not depend on the tokens and
+ *                                stay valid; the token-dependent per-position
+ *                                outputs of that window are unspecified).
  *   uniforms                     [B, K] float32 draws u_t in [0,1]; may be NULL
  *                                only for PPOW_VERIFY_GREEDY
  *   ref_logprob                  [B] float32 or NULL.  When given it is the

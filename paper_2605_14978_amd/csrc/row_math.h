@@ -300,9 +300,14 @@ __device__ __forceinline__ DraftedToken load_drafted_token(const RowArgs &args, 
         d.tok = -1; d.a_tok = 0.f; d.b_tok = 0.f;
         return d;
     }
-    d.tok = args.tokens[row];
-    d.a_tok = S::load1(static_cast<const elem *>(args.target) + row * args.V + d.tok);
-    d.b_tok = S::load1(static_cast<const elem *>(args.draft) + row * args.V + d.tok);
+    // A token outside [0, V) must not become an address: element 0 is read in its place and
+    // the position is marked (tok = -2), which the window epilogue turns into accepted_len = -1.
+    const int tok = args.tokens[row];
+    const bool in_range = static_cast<uint32_t>(tok) < static_cast<uint32_t>(args.V);
+    const int at = in_range ? tok : 0;
+    d.tok = in_range ? tok : -2;
+    d.a_tok = S::load1(static_cast<const elem *>(args.target) + row * args.V + at);
+    d.b_tok = S::load1(static_cast<const elem *>(args.draft) + row * args.V + at);
     return d;
 }
 
@@ -356,7 +361,7 @@ __device__ __forceinline__ void finish_row(const RowArgs &args, int64_t row, con
     rec.accept = accept;
     rec.reverse_kl = reverse_kl;
     rec.alignment = alignment;
-    rec.pad0 = 0.f;
+    rec.bad_token = (tok == -2) ? 1u : 0u;
     rec.pad1 = 0.f;
     args.records[row] = rec;
 

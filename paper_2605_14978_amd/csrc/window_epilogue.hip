@@ -29,8 +29,10 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
 
     float v = 0.f, gap = 0.f, logp = 0.f, rkl = 0.f, align = 0.f;
     int accept = 0;
+    bool bad_token = false;
     if (active) {
         const RowRecord rec = args.records[window * args.K + t];
+        bad_token = rec.bad_token != 0u;
         v = rec.criticality;
         gap = rec.gap;
         logp = rec.logp_tok;
@@ -45,7 +47,11 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
     unsigned long long bits = ballot >> group_base;
     unsigned long long rejected = ~bits;
     if (args.K < 64) rejected |= (1ull << args.K);          // position K always "rejects"
-    const int k = rejected ? __builtin_ctzll(rejected) : 64;
+    int k = rejected ? __builtin_ctzll(rejected) : 64;
+    // a drafted token outside [0, V) anywhere in the window: no accepted length, no reward
+    const unsigned long long group_mask = group == 64 ? ~0ull : ((1ull << group) - 1ull);
+    const bool invalid = ((__ballot(active && bad_token) >> group_base) & group_mask) != 0ull;
+    if (invalid) k = -1;
 
     // fixed-order sums over the group
     for (int off = group >> 1; off > 0; off >>= 1) {
@@ -60,7 +66,7 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
         const float kf = static_cast<float>(k);
         const float delta = args.ref_logprob ? (args.ref_logprob[window] - logp) : gap;
         args.accepted_len[window] = k;
-        args.r_speedup[window] = kf / fmaf(kf, args.cost_ratio, 1.0f);
+        args.r_speedup[window] = invalid ? 0.f : kf / fmaf(kf, args.cost_ratio, 1.0f);
         args.r_proximity[window] = (k == 0 && delta < args.prox_eps) ? args.prox_eta : 0.f;
         args.adaw_score[window] = v / static_cast<float>(args.K);
         if (args.delta) args.delta[window] = delta;

@@ -368,6 +368,28 @@ def test_second_pass_rows_longer_than_one_slice_and_many_rows_per_cluster():
     assert 0 < ref.accepted_len.mean() < 5
 
 
+@pytest.mark.parametrize("expected_accept", [False, True])
+def test_tokens_outside_the_vocabulary_mark_their_window_and_nothing_else(expected_accept):
+    """The device, not the host, sees the drafted tokens: an out-of-range one must not be used
+    as an address (the kernel substitutes element 0) and its window reports accepted_len = -1."""
+    B, K, V = 12, 3, 5003
+    d = _random_inputs(B, K, V, torch.float32, seed=31)
+    good = dict(d)
+    tok = d["draft_tokens"].clone()
+    bad_windows = {1: (0, V), 4: (2, -1), 7: (1, 2 ** 30), 11: (0, -2 ** 31)}
+    for b, (t, value) in bad_windows.items():
+        tok[b, t] = value
+    d["draft_tokens"] = tok
+    gpu = run_gpu(d, cost_ratio=0.05, verify="rejection", expected_accept=expected_accept)
+    ref = run_oracle(good, cost_ratio=0.05, verify="rejection", expected_accept=expected_accept)
+    k = gpu.accepted_len.cpu().numpy()
+    ok = np.array([b not in bad_windows for b in range(B)])
+    assert np.all(k[~ok] == -1) and np.array_equal(k[ok], ref.accepted_len[ok])
+    assert np.all(gpu.r_speedup.cpu().numpy()[~ok] == 0) and np.all(gpu.r_proximity.cpu().numpy()[~ok] == 0)
+    np.testing.assert_allclose(gpu.r_speedup.cpu().numpy()[ok], ref.r_speedup[ok], rtol=1e-6)
+    np.testing.assert_allclose(gpu.adaw_score.cpu().numpy(), ref.adaw_score, rtol=RTOL["f32"], atol=1e-6)
+
+
 def test_calls_on_a_side_stream_and_back_to_back_calls_sharing_a_workspace():
     """The library enqueues on the stream it is given; calls that share a workspace on one
     stream run one after another and must not disturb each other."""
