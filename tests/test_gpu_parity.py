@@ -206,6 +206,31 @@ def test_second_pass_on_rows_whose_reference_keeps_moving(dtype):
     assert ppow.last_row_kernel() == "cluster"
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_option_combinations(seed):
+    """Seeded random shapes and option sets, second pass and policy terms included, down to
+    vocabularies shorter than one 16-byte chunk."""
+    rng = np.random.default_rng(1000 + seed)
+    V = int(rng.choice([2, 3, 5, 8, 13, 64, 127, 1000, 2051, 5000, 12289, 33001, 70001]))
+    K = int(rng.choice([1, 2, 3, 4, 7, 10, 16, 33]))
+    B = int(rng.integers(1, 7)) * (2 if K <= 4 else 1)
+    dtype = torch.float32 if rng.random() < 0.5 else torch.bfloat16
+    greedy = bool(rng.random() < 0.4)
+    group = int(rng.choice([0, 1, 2])) if B % 2 == 0 else int(rng.choice([0, 1]))
+    d = _random_inputs(B, K, V, dtype, seed=seed, sigma=float(rng.choice([0.2, 1.0, 3.0])), greedy=greedy,
+                       scale=float(rng.choice([0.5, 3.0, 8.0])))
+    if greedy:                      # let some prefixes survive
+        d["draft_tokens"] = torch.where(torch.rand(B, K, device=DEV) < 0.6,
+                                        d["target_logits"].float().argmax(-1).to(torch.int32),
+                                        d["draft_tokens"]).contiguous()
+    kw = {}
+    if group:
+        kw["rollout_group"] = group
+    _check(d, V, verify="greedy" if greedy else "rejection",
+           expected_accept=bool(rng.random() < 0.6), policy_terms=bool(rng.random() < 0.5),
+           cost_ratio=float(rng.choice([0.01, 0.03, 0.5])), **kw)
+
+
 def test_uniform_target_has_zero_confidence():
     V = 2048
     a = torch.full((2, 2, V), 1.5)
