@@ -47,7 +47,9 @@ enum {
     /* also compute sum_y min(P_t(y), Q_t(y)), the expected acceptance probability
      * of Appendix B.1; it needs normalised probabilities, hence a second pass over
      * each row pair, served from LDS (a cluster of workgroups shares a row pair)
-     * where the device allows a cooperative launch, from memory otherwise */
+     * where the device allows a cooperative launch, from memory otherwise -- also
+     * while the stream is being captured into a graph, since a cooperative launch
+     * cannot be recorded */
     PPOW_FLAG_EXPECTED_ACCEPT = 1u,
     /* also compute the forward values of the policy-loss terms from the same pass:
      * KL(Q_t || P_t), the target-anchored regulariser of Section 4.1 / Appendix A.2,

@@ -600,6 +600,14 @@ hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, 
                               hipStream_t stream, bool *launched) {
     *launched = false;
     if (rows == 0) return hipSuccess;
+    // A cooperative launch cannot be recorded into a graph: while the stream is being captured
+    // the caller gets the one-workgroup-per-row kernel (second pass from memory), which can.
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+        (void)hipGetLastError();        // e.g. the null stream while another stream captures
+        capture = hipStreamCaptureStatusNone;
+    }
+    if (capture != hipStreamCaptureStatusNone) return hipSuccess;
     const DeviceInfo dev = device_info();
     if (!dev.cooperative || dev.cus < 1) return hipSuccess;
 

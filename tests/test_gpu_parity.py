@@ -477,6 +477,44 @@ def test_scoring_and_selection_replay_from_a_hip_graph():
         assert torch.equal(sel.indices, eager_idx), replay
 
 
+def test_second_pass_can_be_captured_into_a_hip_graph():
+    """A cooperative launch cannot be recorded, so under capture the second pass runs from
+    memory; the replays must agree with the oracle like the eager (on-chip) result does."""
+    V = 30011
+    d = _random_inputs(24, 3, V, torch.float32, seed=41, sigma=1.0)
+    ref = run_oracle(d, cost_ratio=0.05, verify="rejection", expected_accept=True)
+    d, _, changed = _keep_decisions_clear(d, ref, "rejection")
+    if changed:
+        ref = run_oracle(d, cost_ratio=0.05, verify="rejection", expected_accept=True)
+    flags = ppow.PPOW_FLAG_EXPECTED_ACCEPT
+    opt = ("delta", "kl", "confidence", "accept_prob", "logp_target_tok", "logp_draft_tok", "expected_accept")
+    bufs = ppow.ScoreBuffers(24, 3, V, ppow.PPOW_F32, DEV, opt, flags)
+
+    def step():
+        ppow.ppow_score_windows(d["draft_logits"], d["target_logits"], d["draft_tokens"], d["uniforms"],
+                                cost_ratio=0.05, flags=flags, buffers=bufs)
+
+    step()
+    torch.cuda.synchronize()
+    assert ppow.last_row_kernel() == "cluster"
+    compare(bufs, ref, "f32", V, True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    assert ppow.last_row_kernel() == "row"
+    for replay in range(3):
+        for t in (bufs.accepted_len, bufs.adaw_score, bufs.expected_accept, bufs.kl):
+            t.zero_()                                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        compare(bufs, ref, "f32", V, True)
+        assert bufs.status() == 0
+
+
 def test_results_are_bitwise_reproducible():
     w = WORKLOADS["rejection_bf16_128k"].scaled(16)
     d = generate(w, device=DEV)
