@@ -49,7 +49,8 @@ enum {
      * each row pair, served from LDS (a cluster of workgroups shares a row pair)
      * where the device allows a cooperative launch, from memory otherwise -- also
      * while the stream is being captured into a graph, since a cooperative launch
-     * cannot be recorded */
+     * cannot be recorded.  Calls with this flag on different streams of one
+     * device run one after another (each such kernel needs the whole device) */
     PPOW_FLAG_EXPECTED_ACCEPT = 1u,
     /* also compute the forward values of the policy-loss terms from the same pass:
      * KL(Q_t || P_t), the target-anchored regulariser of Section 4.1 / Appendix A.2,

@@ -22,6 +22,8 @@
 //           pass 2 from registers/LDS; publish the partial min-sum;
 //           member (e mod S) polls the S min-sums, adds them in member order and finishes
 //           the row.  Fixed order => bitwise reproducible.
+#include <mutex>
+
 #include "row_math.h"
 
 namespace ppow {
@@ -550,6 +552,20 @@ DeviceInfo device_info() {
     return d;
 }
 
+// Two cluster kernels must never share the GPU: each assumes that all of its workgroups are
+// resident, and two of them that are each half resident would wait for each other until the
+// bounded waits expire.  Launches on different streams are therefore chained through an event
+// per device: a launch waits for the previous cluster kernel on that device to finish.
+struct ClusterChain {
+    std::mutex lock;
+    hipEvent_t done[64] = {};
+    bool have[64] = {};
+};
+ClusterChain &cluster_chain() {
+    static ClusterChain chain;       // lives until the process ends
+    return chain;
+}
+
 template <int DTYPE, bool REV>
 hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t stream, bool *launched) {
     const void *fn = reinterpret_cast<const void *>(row_cluster_kernel<DTYPE, REV>);
@@ -576,6 +592,19 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
     if (clusters < 1) return hipSuccess;
     ca.clusters = static_cast<int32_t>(clusters);
 
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    ClusterChain &chain = cluster_chain();
+    std::lock_guard<std::mutex> guard(chain.lock);
+    if (!chain.have[dev]) {
+        err = hipEventCreateWithFlags(&chain.done[dev], hipEventDisableTiming);
+        if (err != hipSuccess) return err;
+        chain.have[dev] = true;
+    } else {
+        err = hipStreamWaitEvent(stream, chain.done[dev], 0);
+        if (err != hipSuccess) return err;
+    }
+
     // status, counters and every slot tag start from zero on every call (a fill kernel, not a
     // memset node): a tag left by an earlier call must never look like this call's
     const int words = static_cast<int>(kClusterScratchBytes / 4);
@@ -587,6 +616,8 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
     void *params[] = {&ca};
     err = hipLaunchCooperativeKernel(fn, dim3(static_cast<unsigned>(clusters * ca.members)),
                                      dim3(kThreads), params, lds_bytes, stream);
+    if (err != hipSuccess) return err;
+    err = hipEventRecord(chain.done[dev], stream);
     if (err != hipSuccess) return err;
     *launched = true;
     return hipSuccess;

@@ -441,6 +441,32 @@ def test_calls_on_a_side_stream_and_back_to_back_calls_sharing_a_workspace():
                           oracle.select_windows(bufs.adaw_score.cpu().numpy().astype(np.float64), w.M))
 
 
+def test_second_pass_calls_on_two_streams_at_once():
+    """Each on-chip second-pass kernel needs the whole GPU, so the library chains such launches
+    across streams; calls issued back to back on two streams must both come out right."""
+    V, K = 50021, 4
+    flags = ppow.PPOW_FLAG_EXPECTED_ACCEPT
+    opt = ("kl", "expected_accept", "accept_prob")
+    cases = []
+    for seed in (51, 52):
+        d = _random_inputs(600, K, V, torch.float32, seed=seed, sigma=0.8)
+        ref = run_oracle(d, cost_ratio=0.05, verify="rejection", expected_accept=True)
+        d, _, changed = _keep_decisions_clear(d, ref, "rejection")
+        if changed:
+            ref = run_oracle(d, cost_ratio=0.05, verify="rejection", expected_accept=True)
+        cases.append((d, ref, ppow.ScoreBuffers(600, K, V, ppow.PPOW_F32, DEV, opt, flags), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for d, ref, bufs, stream in cases:
+            ppow.ppow_score_windows(d["draft_logits"], d["target_logits"], d["draft_tokens"], d["uniforms"],
+                                    cost_ratio=0.05, flags=flags, buffers=bufs, stream=stream)
+            assert ppow.last_row_kernel() == "cluster"
+    torch.cuda.synchronize()
+    for d, ref, bufs, stream in cases:
+        assert bufs.status() == 0
+        compare(bufs, ref, "f32", V, True)
+
+
 def test_scoring_and_selection_replay_from_a_hip_graph():
     """The single-pass path allocates nothing and records no memset node, so it can be captured
     once and replayed; every replay must reproduce the eager result bit for bit, with eager work
