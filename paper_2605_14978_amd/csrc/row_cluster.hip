@@ -185,7 +185,7 @@ void row_cluster_kernel(ClusterArgs ca) {
         const elem *row_a = static_cast<const elem *>(args.target) + row * args.V;
         const elem *row_b = static_cast<const elem *>(args.draft) + row * args.V;
         const uintptr_t addr = reinterpret_cast<uintptr_t>(row_a);
-        int head = static_cast<int>(((16u - (addr & 15u)) & 15u) / sizeof(elem));
+        int head = static_cast<int>(((kRowAlign - (addr & (kRowAlign - 1u))) & (kRowAlign - 1u)) / sizeof(elem));
         head = head < V ? head : V;
         const int nchunks = (V - head) / VEC;
         const int tail_begin = head + nchunks * VEC;

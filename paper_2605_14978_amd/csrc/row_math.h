@@ -82,6 +82,14 @@ struct Storage<PPOW_BF16> {
     }
 };
 
+// The vector body of a row starts at the first address of the row that is a multiple of this
+// (a cache line, so that a wave's 1 KiB reads do not straddle lines); the elements before it
+// and after the last whole 16-byte chunk go through scalar loads.  PPOW_ROW_ALIGN >= 16.
+#ifndef PPOW_ROW_ALIGN
+#define PPOW_ROW_ALIGN 128
+#endif
+constexpr unsigned kRowAlign = PPOW_ROW_ALIGN;
+
 struct LaneState {
     float rho_a, z_a, s1, s2;   // target side
     float rho_b, z_b, s2r;      // draft side (s2r only when the reverse divergence is wanted)

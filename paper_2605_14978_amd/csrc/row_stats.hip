@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     // Elements before the first 16-byte boundary of the row (both rows share the
     // misalignment because both base pointers are 16-byte aligned).
     const uintptr_t addr = reinterpret_cast<uintptr_t>(row_a);
-    int head = static_cast<int>(((16u - (addr & 15u)) & 15u) / sizeof(elem));
+    int head = static_cast<int>(((kRowAlign - (addr & (kRowAlign - 1u))) & (kRowAlign - 1u)) / sizeof(elem));
     head = head < V ? head : V;
     const int nchunks = (V - head) / VEC;
     const int tail_begin = head + nchunks * VEC;
