@@ -192,7 +192,7 @@ void row_cluster_kernel(ClusterArgs ca) {
 
         // this member's slice of the vector body: the first kRegSpan chunks stay in registers,
         // the rest (at most slice_chunks) in LDS
-        const int per = (nchunks + members - 1) / members;
+        const int per = ((nchunks + members - 1) / members + 7) & ~7;   // whole cache lines
         const int c0 = member * per;
         int n = nchunks - c0;
         n = n < per ? n : per;
@@ -650,7 +650,7 @@ hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, 
     int64_t members = (max_chunks + cap_chunks - 1) / cap_chunks;
     if (members < 1) members = 1;
     if (members > kMaxMembers) return hipSuccess;             // row too long for one wavefront of slots
-    const int64_t per = (max_chunks + members - 1) / members;
+    const int64_t per = ((max_chunks + members - 1) / members + 7) & ~int64_t{7};   // as the kernel
     const int64_t in_lds = per > reg_chunks ? per - reg_chunks : 1;
     const int lds_bytes = static_cast<int>(in_lds * 32);
 
