@@ -616,7 +616,10 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
     void *params[] = {&ca};
     err = hipLaunchCooperativeKernel(fn, dim3(static_cast<unsigned>(clusters * ca.members)),
                                      dim3(kThreads), params, lds_bytes, stream);
-    if (err != hipSuccess) return err;
+    if (err != hipSuccess) {            // the runtime will not co-schedule it: use the row kernel
+        (void)hipGetLastError();
+        return hipSuccess;
+    }
     err = hipEventRecord(chain.done[dev], stream);
     if (err != hipSuccess) return err;
     *launched = true;
