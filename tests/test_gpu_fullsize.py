@@ -17,7 +17,7 @@ from parity import check_selection, compare, run_oracle
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-SAMPLE = 48
+SAMPLE = 512
 
 
 def _score_chunk(w, d, sbuf):
