@@ -112,8 +112,12 @@ size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype
  *
  *   draft_logits, target_logits  [B, K, V] dense row-major, V contiguous, `dtype`
  *                                storage, base pointers 16-byte aligned.  Logits
- *                                must be finite.  P_t = softmax(target row),
- *                                Q_t = softmax(draft row), temperature 1.
+ *                                must be finite; a window with a NaN or an
+ *                                infinity in any of its rows is reported with
+ *                                accepted_len = -2, zero rewards and adaw_score = 0
+ *                                (its other outputs are unspecified).
+ *                                P_t = softmax(target row), Q_t = softmax(draft
+ *                                row), temperature 1.
  *   draft_tokens                 [B, K] int32, 0 <= token < V.  The host cannot
  *                                see them, so the device checks: a token outside
  *                                the range is never used as an address; its

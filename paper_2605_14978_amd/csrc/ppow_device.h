@@ -17,7 +17,8 @@ struct RowRecord {
     int32_t accept;      // verification outcome of this position     (Appendix C.1)
     float reverse_kl;    // KL(Q_t || P_t)                            (Section 4.1, Appendix A.2)
     float alignment;     // exp(d) - d - 1, d = log P_t(tok) - log Q_t(tok)   (Appendix E)
-    uint32_t bad_token;  // 1 if the drafted token of this position was outside [0, V)
+    uint32_t bad_token;  // bit 0: the drafted token of this position was outside [0, V);
+                         // bit 1: the logit rows of this position were not all finite
     float pad1;
 };
 static_assert(sizeof(RowRecord) == 32, "records are 32 bytes");

@@ -369,7 +369,20 @@ __device__ __forceinline__ void finish_row(const RowArgs &args, int64_t row, con
     rec.accept = accept;
     rec.reverse_kl = reverse_kl;
     rec.alignment = alignment;
-    rec.bad_token = (tok == -2) ? 1u : 0u;
+    // A NaN or an infinity anywhere in either row ends up in one of the row sums.  The test is
+    // on bit patterns the compiler cannot trace back to a float: the build lets it assume that
+    // floats are never NaN, and it would fold a test it recognised as one for NaN away.
+    auto opaque_bits = [](float x) {
+        uint32_t u = __builtin_bit_cast(uint32_t, x);
+        asm volatile("" : "+v"(u));
+        return u;
+    };
+    const uint32_t exponent_bits = 0x7f800000u;
+    const bool finite = (opaque_bits(t.z_a) & exponent_bits) != exponent_bits &&
+                        (opaque_bits(t.z_b) & exponent_bits) != exponent_bits &&
+                        (opaque_bits(t.s1) & exponent_bits) != exponent_bits &&
+                        (opaque_bits(t.s2) & exponent_bits) != exponent_bits;
+    rec.bad_token = ((tok == -2) ? 1u : 0u) | (finite ? 0u : 2u);
     rec.pad1 = 0.f;
     args.records[row] = rec;
 

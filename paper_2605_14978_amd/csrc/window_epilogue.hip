@@ -29,10 +29,11 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
 
     float v = 0.f, gap = 0.f, logp = 0.f, rkl = 0.f, align = 0.f;
     int accept = 0;
-    bool bad_token = false;
+    bool bad_token = false, bad_logits = false;
     if (active) {
         const RowRecord rec = args.records[window * args.K + t];
-        bad_token = rec.bad_token != 0u;
+        bad_token = (rec.bad_token & 1u) != 0u;
+        bad_logits = (rec.bad_token & 2u) != 0u;
         v = rec.criticality;
         gap = rec.gap;
         logp = rec.logp_tok;
@@ -50,8 +51,10 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
     int k = rejected ? __builtin_ctzll(rejected) : 64;
     // a drafted token outside [0, V) anywhere in the window: no accepted length, no reward
     const unsigned long long group_mask = group == 64 ? ~0ull : ((1ull << group) - 1ull);
-    const bool invalid = ((__ballot(active && bad_token) >> group_base) & group_mask) != 0ull;
-    if (invalid) k = -1;
+    const bool not_finite = ((__ballot(active && bad_logits) >> group_base) & group_mask) != 0ull;
+    const bool invalid = not_finite ||
+                         ((__ballot(active && bad_token) >> group_base) & group_mask) != 0ull;
+    if (invalid) k = not_finite ? -2 : -1;      // logits that are not finite: no score either
 
     // fixed-order sums over the group
     for (int off = group >> 1; off > 0; off >>= 1) {
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
         args.accepted_len[window] = k;
         args.r_speedup[window] = invalid ? 0.f : kf / fmaf(kf, args.cost_ratio, 1.0f);
         args.r_proximity[window] = (k == 0 && delta < args.prox_eps) ? args.prox_eta : 0.f;
-        args.adaw_score[window] = v / static_cast<float>(args.K);
+        args.adaw_score[window] = not_finite ? 0.f : v / static_cast<float>(args.K);
         if (args.delta) args.delta[window] = delta;
         if (args.reverse_kl_mean) args.reverse_kl_mean[window] = rkl / static_cast<float>(args.K);
         if (args.alignment_mean) args.alignment_mean[window] = align / static_cast<float>(args.K);

@@ -415,6 +415,30 @@ def test_tokens_outside_the_vocabulary_mark_their_window_and_nothing_else(expect
     np.testing.assert_allclose(gpu.adaw_score.cpu().numpy(), ref.adaw_score, rtol=RTOL["f32"], atol=1e-6)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("expected_accept", [False, True])
+def test_windows_with_non_finite_logits_are_marked(dtype, expected_accept):
+    """Finite logits are a precondition; a NaN or an infinity must still be visible in the
+    result (accepted_len = -2, no reward, score 0) and must not disturb other windows."""
+    B, K, V = 10, 3, 9001
+    d = _random_inputs(B, K, V, dtype, seed=61)
+    clean = {k: (None if v is None else v.clone()) for k, v in d.items()}
+    d["target_logits"][2, 1, 4000] = float("nan")
+    d["draft_logits"][5, 0, 17] = float("inf")
+    d["target_logits"][8, 2, V - 1] = float("-inf")
+    d["draft_logits"][9, 2, 0] = float("-inf")
+    bad = [2, 5, 8, 9]
+    gpu = run_gpu(d, cost_ratio=0.05, verify="rejection", expected_accept=expected_accept)
+    ref = run_oracle(clean, cost_ratio=0.05, verify="rejection", expected_accept=expected_accept)
+    k = gpu.accepted_len.cpu().numpy()
+    ok = np.array([b not in bad for b in range(B)])
+    assert np.all(k[~ok] == -2) and np.array_equal(k[ok], ref.accepted_len[ok])
+    for name in ("r_speedup", "r_proximity", "adaw_score"):
+        assert np.all(getattr(gpu, name).cpu().numpy()[~ok] == 0), name
+    np.testing.assert_allclose(gpu.adaw_score.cpu().numpy()[ok], ref.adaw_score[ok],
+                               rtol=RTOL[dtype_name(d["target_logits"])], atol=1e-6)
+
+
 def test_calls_on_a_side_stream_and_back_to_back_calls_sharing_a_workspace():
     """The library enqueues on the stream it is given; calls that share a workspace on one
     stream run one after another and must not disturb each other."""
