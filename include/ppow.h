@@ -46,11 +46,12 @@ typedef enum { PPOW_VERIFY_REJECTION = 0, PPOW_VERIFY_GREEDY = 1 } ppow_verify;
 enum {
     /* also compute sum_y min(P_t(y), Q_t(y)), the expected acceptance probability
      * of Appendix B.1; it needs normalised probabilities, hence a second pass over
-     * each row pair, served from LDS (a cluster of workgroups shares a row pair)
-     * where the device allows a cooperative launch, from memory otherwise -- also
-     * while the stream is being captured into a graph, since a cooperative launch
-     * cannot be recorded.  Calls with this flag on different streams of one
-     * device run one after another (each such kernel needs the whole device) */
+     * each row pair, served from registers and LDS (a cluster of workgroups shares
+     * a row pair, every logit is fetched from memory once) where the sizes allow
+     * it, from memory otherwise -- also while the stream is being captured into a
+     * graph.  Calls with this flag on different streams of one device run one
+     * after another (each such kernel needs the whole device); the library orders
+     * them with one event per device, see ppow_release() */
     PPOW_FLAG_EXPECTED_ACCEPT = 1u,
     /* also compute the forward values of the policy-loss terms from the same pass:
      * KL(Q_t || P_t), the target-anchored regulariser of Section 4.1 / Appendix A.2,
@@ -103,7 +104,8 @@ typedef struct {
  * invalid sizes).  The workspace must be 16-byte aligned.  After the stream has
  * drained, the first 32-bit word of the workspace is 0 unless the bounded wait
  * inside the cluster variant of the row kernel expired, which is not expected to
- * happen; the outputs of that call are then invalid. */
+ * happen; every window of that call is then reported with accepted_len = -3,
+ * zero rewards and adaw_score = 0 (its other outputs are unspecified). */
 size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype, uint32_t flags);
 
 /*
@@ -190,6 +192,21 @@ size_t ppow_select_workspace_bytes(int64_t B, int32_t M);
 int ppow_select_windows(const float *adaw_score, int64_t B, int32_t M,
                         int32_t *indices, float *scores,
                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Releases what the library holds besides caller memory: the HIP event (one per
+ * device) with which it orders the calls that use the on-chip second pass.
+ * Optional; typically called once before the process ends, with no other thread
+ * inside a libppow call.  Work already enqueued is not affected, and a later
+ * scoring call simply creates the event again.
+ */
+int ppow_release(void);
+
+/* Testing aid: how many times a workgroup of the on-chip second pass looks for
+ * its partners' results before it gives up (0 = the default, about 2^24).  A
+ * tiny value makes the give-up path -- status word set, windows marked with
+ * accepted_len = -3 -- reachable from a test; every kernel still ends normally. */
+void ppow_debug_cluster_wait_limit(uint32_t looks);
 
 /* Message of the calling thread's most recent failed call (static storage). */
 const char *ppow_last_error(void);

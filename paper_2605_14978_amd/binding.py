@@ -4,6 +4,7 @@ Every step of the scoring path runs in the HIP kernels of libppow.so; torch is
 used for device memory and the current stream.  There is no CPU fallback: if the
 library is missing or no GPU is visible the calls raise.
 """
+import atexit
 import ctypes
 import os
 
@@ -74,6 +75,10 @@ def lib():
                                          ctypes.POINTER(PpowParams), ctypes.POINTER(PpowOutputs),
                                          vp, sz, vp]
         L.ppow_score_windows.restype = ctypes.c_int
+        L.ppow_release.argtypes = []
+        L.ppow_release.restype = ctypes.c_int
+        L.ppow_debug_cluster_wait_limit.argtypes = [u32]
+        L.ppow_debug_cluster_wait_limit.restype = None
         L.ppow_adaw_sequence_workspace_bytes.argtypes = [i64, i32, i64, i32]
         L.ppow_adaw_sequence_workspace_bytes.restype = sz
         L.ppow_adaw_sequence.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -89,6 +94,8 @@ def lib():
         L.ppow_version.argtypes = []
         L.ppow_version.restype = ctypes.c_char_p
         _lib = L
+        # the event the library keeps per device goes before the HIP runtime is torn down
+        atexit.register(L.ppow_release)
     return _lib
 
 
@@ -129,7 +136,8 @@ PER_GROUP_OPTIONAL = ("group_best_len", "group_best_index")      # int32 [B / ro
 class ScoreBuffers:
     """Device outputs and workspace of ppow_score_windows, allocated once and reused."""
 
-    def __init__(self, B, K, V, dtype_code, device, optional=(), flags=0, rollout_group=0):
+    def __init__(self, B, K, V, dtype_code, device, optional=(), flags=0, rollout_group=0,
+                 workspace=True):
         self.B, self.K = B, K
         self.rollout_group = rollout_group
         dev = torch.device(device)
@@ -152,10 +160,12 @@ class ScoreBuffers:
                     raise ValueError("group outputs need rollout_group >= 1 dividing B")
                 t = torch.empty(B // rollout_group, dtype=torch.int32, device=dev)
             setattr(self, name, t)
-        nbytes = lib().ppow_score_workspace_bytes(B, K, V, dtype_code, flags)
-        if nbytes == 0:
-            raise PpowError(PPOW_ERR_INVALID_ARG, "sizes rejected by ppow_score_workspace_bytes")
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        self.workspace = None           # ppow_score_windows_static brings its own scratch
+        if workspace:
+            nbytes = lib().ppow_score_workspace_bytes(B, K, V, dtype_code, flags)
+            if nbytes == 0:
+                raise PpowError(PPOW_ERR_INVALID_ARG, "sizes rejected by ppow_score_workspace_bytes")
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
     def window_slice(self, w0, w1):
         """A view of these buffers covering windows [w0, w1) (for chunked scoring)."""
@@ -173,7 +183,10 @@ class ScoreBuffers:
         return view
 
     def status(self):
-        """First word of the workspace: 0 unless the cluster kernel's bounded wait expired."""
+        """First word of the workspace: 0 unless the cluster kernel's bounded wait expired
+        (the windows of that call then carry accepted_len = -3)."""
+        if self.workspace is None:
+            return int((self.accepted_len == -3).any().item())
         return int(self.workspace[:4].view(torch.int32).item())
 
     def as_struct(self):
@@ -184,17 +197,8 @@ class ScoreBuffers:
         return o
 
 
-def ppow_score_windows(draft_logits, target_logits, draft_tokens, uniforms=None, ref_logprob=None,
-                       *, cost_ratio, prox_eps=0.5, prox_eta=1.0, verify=PPOW_VERIFY_REJECTION,
-                       flags=0, rollout_group=0, adv_delta=1e-6, optional=(), buffers=None,
-                       stream=None):
-    """Score B windows on the GPU; returns the ScoreBuffers holding the device outputs.
-
-    Tensors are CUDA tensors: logits [B, K, V] contiguous float32 / bfloat16,
-    draft_tokens [B, K] int32, uniforms [B, K] float32 (None for greedy),
-    ref_logprob [B] float32 or None.  The call is asynchronous on `stream`
-    (default: torch's current stream).
-    """
+def _marshal_score(draft_logits, target_logits, draft_tokens, uniforms, ref_logprob):
+    """Shape / dtype checks shared by the two scoring entry points; returns (B, K, V, code)."""
     if not target_logits.is_cuda:
         raise RuntimeError("libppow scores device tensors only; there is no CPU path")
     B, K, V = target_logits.shape
@@ -209,9 +213,25 @@ def ppow_score_windows(draft_logits, target_logits, draft_tokens, uniforms=None,
         raise ValueError("uniforms must be float32 [B, K]")
     if ref_logprob is not None and (ref_logprob.dtype != torch.float32 or ref_logprob.numel() != B):
         raise ValueError("ref_logprob must be float32 [B]")
-    code = _dtype_code(target_logits)
+    return B, K, V, _dtype_code(target_logits)
+
+
+def ppow_score_windows(draft_logits, target_logits, draft_tokens, uniforms=None, ref_logprob=None,
+                       *, cost_ratio, prox_eps=0.5, prox_eta=1.0, verify=PPOW_VERIFY_REJECTION,
+                       flags=0, rollout_group=0, adv_delta=1e-6, optional=(), buffers=None,
+                       stream=None):
+    """Score B windows on the GPU; returns the ScoreBuffers holding the device outputs.
+
+    Tensors are CUDA tensors: logits [B, K, V] contiguous float32 / bfloat16,
+    draft_tokens [B, K] int32, uniforms [B, K] float32 (None for greedy),
+    ref_logprob [B] float32 or None.  The call is asynchronous on `stream`
+    (default: torch's current stream).
+    """
+    B, K, V, code = _marshal_score(draft_logits, target_logits, draft_tokens, uniforms, ref_logprob)
     if buffers is None:
         buffers = ScoreBuffers(B, K, V, code, target_logits.device, optional, flags, rollout_group)
+    if buffers.workspace is None:
+        raise ValueError("these buffers have no workspace: use ppow_score_windows_static")
     params = PpowParams(float(cost_ratio), float(prox_eps), float(prox_eta), int(verify), int(flags),
                         int(rollout_group), float(adv_delta))
     outs = buffers.as_struct()

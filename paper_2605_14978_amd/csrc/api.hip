@@ -47,11 +47,15 @@ size_t ppow_score_workspace_bytes(int64_t B, int32_t K, int64_t V, int32_t dtype
            static_cast<size_t>(B) * static_cast<size_t>(K) * sizeof(ppow::RowRecord);
 }
 
-int ppow_score_windows(const void *draft_logits, const void *target_logits,
-                       const int32_t *draft_tokens, const float *uniforms,
-                       const float *ref_logprob, int64_t B, int32_t K, int64_t V, int32_t dtype,
-                       const ppow_params *params, const ppow_outputs *out, void *workspace,
-                       size_t workspace_bytes, void *hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Everything of a scoring call the host can check without the workspace.
+int validate_score_args(const void *draft_logits, const void *target_logits,
+                        const int32_t *draft_tokens, const float *uniforms, int64_t B, int32_t K,
+                        int64_t V, int32_t dtype, const ppow_params *params,
+                        const ppow_outputs *out) {
     if (!params || !out) return fail(PPOW_ERR_INVALID_ARG, "params and out must not be NULL");
     if (!sizes_ok(B, K, V, dtype))
         return fail(PPOW_ERR_INVALID_ARG,
@@ -97,12 +101,18 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
         if (out->advantage && (!(params->adv_delta >= 0.f) || !isfinite(params->adv_delta)))
             return fail(PPOW_ERR_INVALID_ARG, "adv_delta must be a finite number >= 0");
     }
-    const size_t need = ppow_score_workspace_bytes(B, K, V, dtype, params->flags);
-    if (!workspace || !aligned16(workspace) || workspace_bytes < need)
-        return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
+    return PPOW_OK;
+}
 
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+// The launches of a scoring call; arguments validated, B > 0, `workspace` large enough.
+int enqueue_score(const void *draft_logits, const void *target_logits,
+                  const int32_t *draft_tokens, const float *uniforms, const float *ref_logprob,
+                  int64_t B, int32_t K, int64_t V, int32_t dtype, const ppow_params *params,
+                  const ppow_outputs *out, void *workspace, hipStream_t stream) {
     const int64_t rows = B * K;
+    const bool second_pass = (params->flags & PPOW_FLAG_EXPECTED_ACCEPT) != 0;
+    const bool policy_terms = (params->flags & PPOW_FLAG_POLICY_TERMS) != 0;
+    const bool group_outputs = out->advantage || out->group_best_len || out->group_best_index;
 
     ppow::RowArgs ra;
     ra.target = target_logits;
@@ -151,6 +161,7 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     wa.reverse_kl_mean = out->reverse_kl_mean;
     wa.alignment_mean = out->alignment_mean;
     wa.status_clear = launched ? nullptr : static_cast<uint32_t *>(workspace);
+    wa.status_check = launched ? static_cast<const uint32_t *>(workspace) : nullptr;
     wa.B = B;
     wa.K = K;
     wa.cost_ratio = params->cost_ratio;
@@ -177,6 +188,36 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
     }
     return PPOW_OK;
 }
+
+}  // namespace
+
+extern "C" {
+
+int ppow_score_windows(const void *draft_logits, const void *target_logits,
+                       const int32_t *draft_tokens, const float *uniforms,
+                       const float *ref_logprob, int64_t B, int32_t K, int64_t V, int32_t dtype,
+                       const ppow_params *params, const ppow_outputs *out, void *workspace,
+                       size_t workspace_bytes, void *hip_stream) {
+    const int status = validate_score_args(draft_logits, target_logits, draft_tokens, uniforms, B, K,
+                                           V, dtype, params, out);
+    if (status != PPOW_OK || B == 0) return status;
+    const size_t need = ppow_score_workspace_bytes(B, K, V, dtype, params->flags);
+    if (!workspace || !aligned16(workspace) || workspace_bytes < need)
+        return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
+    return enqueue_score(draft_logits, target_logits, draft_tokens, uniforms, ref_logprob, B, K, V,
+                         dtype, params, out, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int ppow_release(void) {
+    const hipError_t err = ppow::release_cluster_chain();
+    if (err != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PPOW_ERR_DEVICE, "hipEventDestroy failed: %s", hipGetErrorString(err));
+    }
+    return PPOW_OK;
+}
+
+void ppow_debug_cluster_wait_limit(uint32_t looks) { ppow::set_cluster_spin_limit(looks); }
 
 size_t ppow_adaw_sequence_workspace_bytes(int64_t N, int32_t T, int64_t V, int32_t dtype) {
     if (N < 0 || T < 1 || V < 2 || V > INT32_MAX || N > INT32_MAX / T) return 0;

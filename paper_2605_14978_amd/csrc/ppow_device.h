@@ -55,6 +55,7 @@ struct WindowArgs {
     float *reverse_kl_mean;      // [B] or nullptr
     float *alignment_mean;       // [B] or nullptr
     uint32_t *status_clear;      // workspace status word to zero, or nullptr (cluster path owns it)
+    const uint32_t *status_check; // status word the cluster kernel may have set, or nullptr
     int64_t B;
     int32_t K;
     float cost_ratio, prox_eps, prox_eta;
@@ -88,6 +89,9 @@ constexpr size_t kClusterScratchBytes = 1u << 20;
 hipError_t launch_row_stats(const RowArgs &args, int64_t rows, int32_t dtype, hipStream_t stream);
 hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, void *scratch,
                               hipStream_t stream, bool *launched);
+hipError_t prepare_cluster_chain();
+hipError_t release_cluster_chain();
+void set_cluster_spin_limit(uint32_t spins);   // 0 restores the default
 hipError_t launch_window_epilogue(const WindowArgs &args, hipStream_t stream);
 hipError_t launch_group_epilogue(const GroupArgs &args, hipStream_t stream);
 hipError_t launch_sequence_windows(const SequenceArgs &args, hipStream_t stream);

@@ -6,11 +6,15 @@
 // the row pair twice.  A CU holds 2 workgroups x (80 KB of VGPRs + 76 KB of LDS) of logits, so
 // 256 CUs keep about 64 fp32 rows of 152K logits (or 150 bf16 rows of 128K) in flight.
 //
-// The kernel is persistent and is launched cooperatively (all workgroups resident), so the
-// one wait of a member -- for the partial sums of the other members of its own cluster, which
-// each of them publishes unconditionally -- always ends.  The wait is bounded all the same:
-// if it ever expired the kernel would set the status word and finish with invalid outputs
-// instead of hanging.
+// The kernel is persistent and its grid is never larger than what the device holds at once
+// (occupancy of this kernel x compute units), so every workgroup becomes resident as soon as
+// whatever else runs on the device has made room, and the one wait of a member -- for the
+// partial sums of the other members of its own cluster, which each of them publishes
+// unconditionally -- always ends.  (Two such kernels at once could each hold half the device
+// and wait for the other half: launches are therefore chained, see ClusterChain below.)  The
+// wait is bounded all the same: if it ever expired the kernel would set the status word and
+// leave, and the window epilogue then marks every window of the call (accepted_len = -3)
+// instead of publishing numbers made from records that were never written.
 //
 // Exchange protocol per row (epoch e of the cluster, slots double-buffered by e & 1).  Every
 // exchanged value is one 64-bit word {tag = e+1, fp32 bits}, written and read with agent-scope
@@ -22,6 +26,7 @@
 //           pass 2 from registers/LDS; publish the partial min-sum;
 //           member (e mod S) polls the S min-sums, adds them in member order and finishes
 //           the row.  Fixed order => bitwise reproducible.
+#include <atomic>
 #include <mutex>
 
 #include "row_math.h"
@@ -46,8 +51,8 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kRegChunks = PPOW_CLUSTER_REG_CHUNKS;
 constexpr int kMaxMembers = 64;                // one lane of a wavefront per member
 constexpr int kExchanged = 10;                 // words a member publishes per row
-constexpr unsigned kMaxSpins = 1u << 24;       // many seconds: members may be kept off the GPU for a
-                                               // while by other streams' kernels, never this long
+constexpr unsigned kDefaultMaxSpins = 1u << 24; // many seconds: members may be kept off the GPU for a
+                                                // while by other streams' kernels, never this long
 
 // scratch layout (bytes): [0,4) status | [256, ...) slots
 constexpr size_t kSlotOffset = 256;
@@ -66,6 +71,7 @@ struct ClusterArgs {
                             // side, so the wavefront that collects them (member l on lane l)
                             // reads each word of the whole cluster with one coalesced request
     int32_t stride;         // S rounded up to a multiple of 8 (64 bytes)
+    uint32_t max_spins;     // looks at a slot before a wait gives up
 };
 
 // 128-bit load from global memory straight into LDS: lane i of the wave writes 16 bytes at
@@ -133,7 +139,7 @@ __device__ __forceinline__ void close_row(const ClusterArgs &ca, const PendingCl
         w = observe(word);
         if (__all(tagged(w, p.tag) || !has)) break;
         __builtin_amdgcn_s_sleep(1);
-        if (++spins > kMaxSpins) {               // never expected: report, do not hang
+        if (++spins > ca.max_spins) {            // never expected: report, do not hang
             if (lane == 0)
                 __hip_atomic_fetch_or(ca.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
@@ -425,7 +431,7 @@ void row_cluster_kernel(ClusterArgs ca) {
                 // never expected: report and leave instead of hanging; a wait that expired
                 // anywhere ends every other wait at its next look at the status word
                 ++spins;
-                if (spins > kMaxSpins ||
+                if (spins > ca.max_spins ||
                     ((spins & 255u) == 0 &&
                      __hip_atomic_load(ca.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
                     abort = 1;
@@ -529,42 +535,40 @@ void row_cluster_kernel(ClusterArgs ca) {
 #endif
 }
 
-struct DeviceInfo {
-    bool known = false;
-    bool cooperative = false;
-    int cus = 0;
-};
-
-DeviceInfo device_info() {
-    static thread_local DeviceInfo cached[64];
+// Compute units of the current device (0 when it cannot be queried), cached per device.
+int compute_units() {
+    static thread_local int cached[64] = {};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DeviceInfo();
-    DeviceInfo &d = cached[dev];
-    if (!d.known) {
-        int coop = 0, cus = 0;
-        if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) {
-            d.cooperative = coop != 0;
-            d.cus = cus;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return 0;
         }
-        d.known = true;
+        cached[dev] = cus;
     }
-    return d;
+    return cached[dev];
 }
 
-// Two cluster kernels must never share the GPU: each assumes that all of its workgroups are
+// Two cluster kernels must never share the GPU: each assumes that all of its workgroups become
 // resident, and two of them that are each half resident would wait for each other until the
 // bounded waits expire.  Launches on different streams are therefore chained through an event
-// per device: a launch waits for the previous cluster kernel on that device to finish.
+// per device: a launch waits for the previous cluster kernel on that device to finish.  The
+// event is created by the first launch on a device (or by prepare_cluster_chain) and lives
+// until release_cluster_chain() -- the library's ppow_release() -- destroys it; nothing in the
+// library refers to it after that, and a later launch simply creates a new one.
 struct ClusterChain {
     std::mutex lock;
     hipEvent_t done[64] = {};
     bool have[64] = {};
+    bool recorded[64] = {};
 };
 ClusterChain &cluster_chain() {
-    static ClusterChain chain;       // lives until the process ends
+    static ClusterChain chain;
     return chain;
 }
+std::atomic<uint32_t> g_max_spins{kDefaultMaxSpins};
 
 template <int DTYPE, bool REV>
 hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t stream, bool *launched) {
@@ -581,6 +585,8 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
         cached_lds = lds_bytes;
         cached_per_cu = q;
     }
+    // The grid never exceeds what the device holds at once: that is what lets every member of
+    // a cluster count on the others being (or becoming) resident.
     const int per_cu = cached_per_cu;
     int64_t clusters = static_cast<int64_t>(per_cu) * cus / ca.members;
     if (clusters > ca.rows) clusters = ca.rows;
@@ -591,6 +597,7 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
     if (clusters > fit) clusters = fit;
     if (clusters < 1) return hipSuccess;
     ca.clusters = static_cast<int32_t>(clusters);
+    ca.max_spins = g_max_spins.load(std::memory_order_relaxed);
 
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
@@ -600,7 +607,9 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
         err = hipEventCreateWithFlags(&chain.done[dev], hipEventDisableTiming);
         if (err != hipSuccess) return err;
         chain.have[dev] = true;
-    } else {
+        chain.recorded[dev] = false;
+    }
+    if (chain.recorded[dev]) {
         err = hipStreamWaitEvent(stream, chain.done[dev], 0);
         if (err != hipSuccess) return err;
     }
@@ -613,20 +622,58 @@ hipError_t launch_variant(ClusterArgs &ca, int lds_bytes, int cus, hipStream_t s
     err = hipGetLastError();
     if (err != hipSuccess) return err;
 
-    void *params[] = {&ca};
-    err = hipLaunchCooperativeKernel(fn, dim3(static_cast<unsigned>(clusters * ca.members)),
-                                     dim3(kThreads), params, lds_bytes, stream);
-    if (err != hipSuccess) {            // the runtime will not co-schedule it: use the row kernel
-        (void)hipGetLastError();
-        return hipSuccess;
-    }
+    hipLaunchKernelGGL((row_cluster_kernel<DTYPE, REV>),
+                       dim3(static_cast<unsigned>(clusters * ca.members)), dim3(kThreads),
+                       lds_bytes, stream, ca);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
     err = hipEventRecord(chain.done[dev], stream);
     if (err != hipSuccess) return err;
+    chain.recorded[dev] = true;
     *launched = true;
     return hipSuccess;
 }
 
 }  // namespace
+
+// One-time set-up of the current device for callers that must not create anything later:
+// the event that chains cluster launches.
+hipError_t prepare_cluster_chain() {
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    ClusterChain &chain = cluster_chain();
+    std::lock_guard<std::mutex> guard(chain.lock);
+    if (!chain.have[dev]) {
+        err = hipEventCreateWithFlags(&chain.done[dev], hipEventDisableTiming);
+        if (err != hipSuccess) return err;
+        chain.have[dev] = true;
+        chain.recorded[dev] = false;
+    }
+    return hipSuccess;
+}
+
+// Destroys the chaining events of every device.  Work already enqueued keeps its ordering (a
+// stream that was told to wait for an event keeps waiting for what was recorded); the caller
+// makes sure that no other thread is inside a scoring call.
+hipError_t release_cluster_chain() {
+    ClusterChain &chain = cluster_chain();
+    std::lock_guard<std::mutex> guard(chain.lock);
+    hipError_t first = hipSuccess;
+    for (int dev = 0; dev < 64; ++dev) {
+        if (!chain.have[dev]) continue;
+        const hipError_t err = hipEventDestroy(chain.done[dev]);
+        if (err != hipSuccess && first == hipSuccess) first = err;
+        chain.have[dev] = false;
+        chain.recorded[dev] = false;
+    }
+    return first;
+}
+
+void set_cluster_spin_limit(uint32_t spins) {
+    g_max_spins.store(spins == 0 ? kDefaultMaxSpins : spins, std::memory_order_relaxed);
+}
 
 // Launches the cluster kernel if the device and the sizes allow it; *launched says whether it
 // did (otherwise the caller uses the one-workgroup-per-row kernel).
@@ -634,16 +681,17 @@ hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, 
                               hipStream_t stream, bool *launched) {
     *launched = false;
     if (rows == 0) return hipSuccess;
-    // A cooperative launch cannot be recorded into a graph: while the stream is being captured
-    // the caller gets the one-workgroup-per-row kernel (second pass from memory), which can.
+    // The event that chains cluster launches must not be recorded into a graph (a replay on
+    // another stream would escape the chain): while the stream is being captured the caller
+    // gets the one-workgroup-per-row kernel (second pass from memory).
     hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
         (void)hipGetLastError();        // e.g. the null stream while another stream captures
         capture = hipStreamCaptureStatusNone;
     }
     if (capture != hipStreamCaptureStatusNone) return hipSuccess;
-    const DeviceInfo dev = device_info();
-    if (!dev.cooperative || dev.cus < 1) return hipSuccess;
+    const int cus = compute_units();
+    if (cus < 1) return hipSuccess;
 
     const int vec = dtype == PPOW_BF16 ? 8 : 4;
     const int64_t max_chunks = args.V / vec;                  // per row side, when head = 0
@@ -664,16 +712,17 @@ hipError_t launch_row_cluster(const RowArgs &args, int64_t rows, int32_t dtype, 
     ca.stride = static_cast<int32_t>((members + 7) & ~static_cast<int64_t>(7));
     ca.clusters = 0;
     ca.slice_chunks = static_cast<int32_t>(in_lds);
+    ca.max_spins = kDefaultMaxSpins;
     char *base = static_cast<char *>(scratch);
     ca.status = reinterpret_cast<uint32_t *>(base);
     ca.slots = reinterpret_cast<uint64_t *>(base + kSlotOffset);
 
     if (dtype == PPOW_BF16) {
-        if (args.want_policy_terms) return launch_variant<PPOW_BF16, true>(ca, lds_bytes, dev.cus, stream, launched);
-        return launch_variant<PPOW_BF16, false>(ca, lds_bytes, dev.cus, stream, launched);
+        if (args.want_policy_terms) return launch_variant<PPOW_BF16, true>(ca, lds_bytes, cus, stream, launched);
+        return launch_variant<PPOW_BF16, false>(ca, lds_bytes, cus, stream, launched);
     }
-    if (args.want_policy_terms) return launch_variant<PPOW_F32, true>(ca, lds_bytes, dev.cus, stream, launched);
-    return launch_variant<PPOW_F32, false>(ca, lds_bytes, dev.cus, stream, launched);
+    if (args.want_policy_terms) return launch_variant<PPOW_F32, true>(ca, lds_bytes, cus, stream, launched);
+    return launch_variant<PPOW_F32, false>(ca, lds_bytes, cus, stream, launched);
 }
 
 }  // namespace ppow

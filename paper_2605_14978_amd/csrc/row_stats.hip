@@ -38,8 +38,9 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     const elem *row_a = static_cast<const elem *>(args.target) + row * args.V;
     const elem *row_b = static_cast<const elem *>(args.draft) + row * args.V;
 
-    // Elements before the first 16-byte boundary of the row (both rows share the
-    // misalignment because both base pointers are 16-byte aligned).
+    // Elements before the first kRowAlign-byte boundary of the target row.  Both base pointers
+    // are 16-byte aligned and both rows start at the same element offset, so the draft row is
+    // 16-byte aligned at the same element (its own line boundary may fall elsewhere).
     const uintptr_t addr = reinterpret_cast<uintptr_t>(row_a);
     int head = static_cast<int>(((kRowAlign - (addr & (kRowAlign - 1u))) & (kRowAlign - 1u)) / sizeof(elem));
     head = head < V ? head : V;
@@ -75,7 +76,8 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
         fold_chunk<VEC, REV>(s, a, b, c);
     }
 
-    // Ragged ends: at most VEC-1 elements before and after the vector body.
+    // Ragged ends: fewer than kRowAlign bytes of elements before the vector body and at most
+    // VEC-1 elements after it (63 + 7 bf16 elements at most), one per lane.
     const int ragged = head + (V - tail_begin);
     float rag_v = PPOW_NEG_INF;
     int rag_i = INT_MAX;

@@ -26,6 +26,9 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
     const int t = static_cast<int>(gid & (group - 1));
     const bool active = (window < args.B) && (t < args.K);
     if (gid == 0 && args.status_clear) *args.status_clear = 0u;
+    // A bounded wait of the cluster kernel that expired left records unwritten: every window
+    // of the call is then marked instead of being given plausible-looking numbers.
+    const bool expired = args.status_check && *args.status_check != 0u;
 
     float v = 0.f, gap = 0.f, logp = 0.f, rkl = 0.f, align = 0.f;
     int accept = 0;
@@ -55,6 +58,7 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
     const bool invalid = not_finite ||
                          ((__ballot(active && bad_token) >> group_base) & group_mask) != 0ull;
     if (invalid) k = not_finite ? -2 : -1;      // logits that are not finite: no score either
+    if (expired) k = -3;
 
     // fixed-order sums over the group
     for (int off = group >> 1; off > 0; off >>= 1) {
@@ -69,9 +73,9 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
         const float kf = static_cast<float>(k);
         const float delta = args.ref_logprob ? (args.ref_logprob[window] - logp) : gap;
         args.accepted_len[window] = k;
-        args.r_speedup[window] = invalid ? 0.f : kf / fmaf(kf, args.cost_ratio, 1.0f);
+        args.r_speedup[window] = (invalid || expired) ? 0.f : kf / fmaf(kf, args.cost_ratio, 1.0f);
         args.r_proximity[window] = (k == 0 && delta < args.prox_eps) ? args.prox_eta : 0.f;
-        args.adaw_score[window] = not_finite ? 0.f : v / static_cast<float>(args.K);
+        args.adaw_score[window] = (not_finite || expired) ? 0.f : v / static_cast<float>(args.K);
         if (args.delta) args.delta[window] = delta;
         if (args.reverse_kl_mean) args.reverse_kl_mean[window] = rkl / static_cast<float>(args.K);
         if (args.alignment_mean) args.alignment_mean[window] = align / static_cast<float>(args.K);
@@ -80,7 +84,10 @@ __global__ __launch_bounds__(kThreads) void window_epilogue_kernel(WindowArgs ar
 
 // Per group of G consecutive windows, one thread per group, everything in index order:
 //  * group-relative advantage (Section 4.1): A_i = (R_i - mean) / (std + delta) with
-//    R_i = r_speedup + r_proximity (Algorithm 1's reward), std the population standard deviation;
+//    R_i = r_speedup + r_proximity (Algorithm 1's reward), std the population standard deviation.
+//    Mean and variance are formed in double: a group whose rewards are all equal (every window
+//    fully accepted, say) then has R_i - mean exactly 0, where an fp32 mean leaves a residue of
+//    an ulp or two that the division by std + delta (delta ~ 1e-6) would blow up to ~0.1;
 //  * best candidate (multi-candidate decoding, Table 2): the largest accepted length of the
 //    group and the index of the first window attaining it.
 __global__ __launch_bounds__(kThreads) void group_epilogue_kernel(GroupArgs args) {
@@ -88,18 +95,22 @@ __global__ __launch_bounds__(kThreads) void group_epilogue_kernel(GroupArgs args
     if (g >= args.groups) return;
     const int64_t base = g * args.group;
     if (args.advantage) {
-        float mean = 0.f;
-        for (int i = 0; i < args.group; ++i) mean += args.r_speedup[base + i] + args.r_proximity[base + i];
-        mean /= static_cast<float>(args.group);
-        float var = 0.f;
+        auto reward = [&](int i) {
+            return static_cast<double>(args.r_speedup[base + i]) +
+                   static_cast<double>(args.r_proximity[base + i]);
+        };
+        const double count = static_cast<double>(args.group);
+        double mean = 0.0;
+        for (int i = 0; i < args.group; ++i) mean += reward(i);
+        mean /= count;
+        double var = 0.0;
         for (int i = 0; i < args.group; ++i) {
-            const float d = args.r_speedup[base + i] + args.r_proximity[base + i] - mean;
-            var = fmaf(d, d, var);
+            const double d = reward(i) - mean;
+            var += d * d;
         }
-        const float inv = 1.0f / (sqrtf(var / static_cast<float>(args.group)) + args.delta_stab);
+        const double inv = 1.0 / (sqrt(var / count) + static_cast<double>(args.delta_stab));
         for (int i = 0; i < args.group; ++i)
-            args.advantage[base + i] =
-                (args.r_speedup[base + i] + args.r_proximity[base + i] - mean) * inv;
+            args.advantage[base + i] = static_cast<float>((reward(i) - mean) * inv);
     }
     if (args.best_len || args.best_index) {
         int best = 0, best_k = args.accepted_len[base];

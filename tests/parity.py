@@ -111,7 +111,18 @@ def compare_advantage(gpu, ref, group, adv_delta, rtol):
     rewards = ref.r_speedup + ref.r_proximity
     expect = np.concatenate([oracle.group_advantage(rewards[i:i + group], adv_delta)
                              for i in range(0, rewards.size, group)])
-    assert_close("advantage", gpu.advantage.cpu(), expect, rtol, atol=1e-5)
+    # The advantage divides by std + delta: the fp32 rounding of the two rewards (~6e-8
+    # relative each) is amplified by |R| / (std + delta), so the floor is set by that, not by
+    # the 1e-6 of the other outputs.
+    std = np.repeat([rewards[i:i + group].std() for i in range(0, rewards.size, group)], group)
+    floor = 4 * 6e-8 * np.abs(rewards).max() / (std + adv_delta)
+    got = np.asarray(gpu.advantage.cpu(), dtype=np.float64)
+    err = np.abs(got - expect)
+    bound = rtol * np.abs(expect) + floor + ATOL
+    worst = int(np.argmax(err - bound))
+    assert np.all(err <= bound), (
+        f"advantage: element {worst} got {got[worst]!r} ref {expect[worst]!r} "
+        f"err {err[worst]:.3e} > bound {bound[worst]:.3e}")
 
 
 def check_selection(gpu_scores, M, oracle_scores=None, rtol=None):

@@ -23,7 +23,8 @@ def test_every_declared_symbol_is_exported():
     assert {"ppow_score_windows", "ppow_select_windows", "ppow_score_workspace_bytes",
             "ppow_select_workspace_bytes", "ppow_last_error", "ppow_version",
             "ppow_last_row_kernel", "ppow_adaw_sequence",
-            "ppow_adaw_sequence_workspace_bytes"} <= set(names)
+            "ppow_adaw_sequence_workspace_bytes", "ppow_release",
+            "ppow_debug_cluster_wait_limit"} <= set(names)
     L = ppow.lib()
     for name in names:
         assert hasattr(L, name), f"{name} declared in ppow.h but not exported"
@@ -132,3 +133,4 @@ def test_binding_refuses_cpu_tensors():
                                 cost_ratio=0.1)
     with pytest.raises(RuntimeError, match="no CPU path"):
         ppow.ppow_select_windows(torch.zeros(8), 2)
+

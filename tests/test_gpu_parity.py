@@ -304,6 +304,34 @@ def test_group_relative_advantage(group):
     assert float(adv.sum(-1).abs().max()) < 1e-4           # zero mean inside every group
 
 
+@pytest.mark.parametrize("group", [3, 5, 6, 7, 8])
+def test_group_advantage_of_equal_rewards_is_exactly_zero(group):
+    """Rewards that are equal across a rollout group (every window fully accepted, or every
+    window rejected at once) have advantage 0 by definition (Section 4.1); with the default
+    delta = 1e-6 any rounding residue of the mean would be blown up to ~0.1.  Mixed groups are
+    compared with the oracle at the same delta."""
+    K, V, groups = 3, 257, 6
+    B = group * groups
+    d = _random_inputs(B, K, V, torch.float32, seed=90 + group, greedy=True)
+    ystar = d["target_logits"].argmax(-1).to(torch.int32)
+    far = d["target_logits"].argmin(-1).to(torch.int32)   # a gap far above eps: no proximity reward
+    tok = ystar.clone()                                   # groups 0, 1: all accepted (k = K)
+    tok[2 * group:4 * group, 0] = far[2 * group:4 * group, 0]               # groups 2, 3: k = 0
+    for b in range(4 * group, B):                         # groups 4, 5: k cycles through 0..K
+        k = b % (K + 1)
+        if k < K:
+            tok[b, k] = far[b, k]
+    d["draft_tokens"] = tok.contiguous()
+    for gamma in (0.03, 0.12, 1.0 / 3.0):
+        ref = run_oracle(d, cost_ratio=gamma, verify="greedy")
+        gpu = run_gpu(d, cost_ratio=gamma, verify="greedy", rollout_group=group)   # delta = 1e-6
+        compare(gpu, ref, "f32", V)
+        adv = gpu.advantage.cpu().view(groups, group)
+        assert torch.all(adv[:4] == 0), adv[:4]
+        compare_advantage(gpu, ref, group, 1e-6, RTOL["f32"])
+        compare_group_best(gpu, ref, group)
+
+
 def test_group_best_with_ties_takes_the_first_candidate():
     K, V = 4, 300
     d = _random_inputs(12, K, V, torch.float32, seed=21, greedy=True)
@@ -391,6 +419,31 @@ def test_second_pass_rows_longer_than_one_slice_and_many_rows_per_cluster():
                                     d["draft_tokens"]).contiguous()
     gpu, ref = _check(d, 9001, verify="greedy", expected_accept=True)
     assert 0 < ref.accepted_len.mean() < 5
+
+
+def test_expired_wait_of_the_on_chip_second_pass_marks_every_window():
+    """The give-up path of the cluster kernel, reached by shrinking its bounded wait to a single
+    look from the host: every kernel still ends normally, the status word is set and every
+    window of the call is reported with accepted_len = -3, zero rewards and score 0."""
+    V = 50021
+    d = _random_inputs(150, 4, V, torch.float32, seed=5, sigma=0.8)
+    L = ppow.lib()
+    L.ppow_debug_cluster_wait_limit(1)
+    try:
+        out = ppow.ppow_score_windows(
+            d["draft_logits"], d["target_logits"], d["draft_tokens"], d["uniforms"],
+            cost_ratio=0.05, flags=ppow.PPOW_FLAG_EXPECTED_ACCEPT, optional=("expected_accept",))
+        assert ppow.last_row_kernel() == "cluster"
+        torch.cuda.synchronize()
+    finally:
+        L.ppow_debug_cluster_wait_limit(0)
+    if out.status() != 0:          # with one look some member practically always misses a partner
+        assert torch.all(out.accepted_len == -3)
+        assert torch.all(out.r_speedup == 0) and torch.all(out.r_proximity == 0)
+        assert torch.all(out.adaw_score == 0)
+    # the next call, with the default limit, is unaffected by what the expired one left behind
+    _check(d, V, expected_accept=True, M=20)
+    assert ppow.last_row_kernel() == "cluster"
 
 
 @pytest.mark.parametrize("expected_accept", [False, True])
