@@ -11,9 +11,15 @@
 //             KL(Q||P) = S2r / Z_b + ln2' * ((rho_a - rho_b) + log2(Z_a / Z_b))
 // with ln2' = 1 / float(log2 e), so that the constant used going in is undone coming out;
 // the few per-row operations that subtract nearly equal numbers are done in double.
-// Identical rows give exactly zero divergence.  A reference only moves when a chunk maximum
-// exceeds it by more than kRescaleGap, which keeps the rescale off the streaming path; the
-// exact row maximum and its first index are tracked separately, branch-free.
+// Identical rows give exactly zero divergence.  The lanes of a wavefront start from a common
+// reference, the largest logit among the wavefront's first chunks (start_reference), and a
+// lane's reference only moves when a chunk maximum exceeds it by more than kRescaleGap: a few
+// times per row, which keeps the rescale off the streaming path.  The gap also bounds the
+// rounding of the exponents: t is rounded to 2^-23 * |t|, so an element that carries much of
+// the probability must not sit far above the reference -- with |t| <= 8 its exponential is
+// good to 2e-7, where |t| ~ 24 would cost 1e-6 of absolute error in the divergences of nearly
+// identical rows (the two rows round differently).  The exact row maximum and its first index
+// are tracked separately, branch-free.
 #pragma once
 
 #include <limits.h>
@@ -24,7 +30,7 @@
 namespace ppow {
 
 constexpr float kLog2e = 1.44269504088896340736f;
-constexpr float kRescaleGap = 24.0f;   // log2 units: partial sums stay below 2^24 * count
+constexpr float kRescaleGap = 8.0f;    // log2 units: partial sums stay below 2^8 * count
 #define PPOW_NEG_INF (-__builtin_huge_valf())
 
 #ifndef PPOW_ROW_NONTEMPORAL
@@ -265,6 +271,25 @@ __device__ __forceinline__ int wave_min(int x) {
                min(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
 }
 
+// Common starting references of a wavefront: the maxima of its lanes' first chunks (-inf for a
+// lane without one).  Every lane of the wavefront must call this, before its first fold.
+__device__ __forceinline__ void start_reference(LaneState &s, float first_max_a, float first_max_b) {
+    const float wa = wave_max(first_max_a);
+    const float wb = wave_max(first_max_b);
+    if (wa != PPOW_NEG_INF) {                 // some lane has a chunk: both rows have elements
+        s.rho_a = wa * kLog2e;
+        s.rho_b = wb * kLog2e;
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ float chunk_max(const float (&x)[VEC]) {
+    float m = x[0];
+#pragma unroll
+    for (int j = 1; j < VEC; ++j) m = fmaxf(m, x[j]);
+    return m;
+}
+
 // Sums of one row pair relative to the references ref_a / ref_b, plus the exact target maximum.
 struct RowTotals {
     float ref_a, ref_b;
@@ -328,8 +353,8 @@ __device__ __forceinline__ void finish_row(const RowArgs &args, int64_t row, con
     const float ln2p = static_cast<float>(ln2p_d);
     const double inv_za = 1.0 / static_cast<double>(t.z_a);
     const double entropy = ln2p_d * (static_cast<double>(log2_za) - t.s1 * inv_za);
-    const double lse_diff = ln2p_d * (static_cast<double>(t.ref_a - t.ref_b) +
-                                      static_cast<double>(fast_log2(t.z_a / t.z_b)));
+    const double lse_diff = ln2p_d * ((static_cast<double>(t.ref_a) - static_cast<double>(t.ref_b)) +
+                                      log2(static_cast<double>(t.z_a) / static_cast<double>(t.z_b)));
     const float kl = fmaxf(static_cast<float>(t.s2 * inv_za - lse_diff), 0.f);
     float conf = static_cast<float>(1.0 - entropy * args.inv_ln_V);
     conf = fminf(fmaxf(conf, 0.f), 1.f);

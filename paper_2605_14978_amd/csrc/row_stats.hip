@@ -53,7 +53,21 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     LaneState s;
     s.reset();
 
-    int c = tid;
+    // Prologue: every lane's first chunk, which also gives the wavefront its starting references.
+    {
+        float a[VEC], b[VEC];
+        float first_a = PPOW_NEG_INF, first_b = PPOW_NEG_INF;
+        if (tid < nchunks) {
+            S::unpack(load_chunk<!SECOND>(pa + tid), a);
+            S::unpack(load_chunk<!SECOND>(pb + tid), b);
+            first_a = chunk_max<VEC>(a);
+            first_b = chunk_max<VEC>(b);
+        }
+        start_reference(s, first_a, first_b);
+        if (tid < nchunks) fold_chunk<VEC, REV>(s, a, b, tid);
+    }
+
+    int c = tid + kThreads;
     for (; c + (kUnroll - 1) * kThreads < nchunks; c += kUnroll * kThreads) {
         raw4 ra[kUnroll], rb[kUnroll];
 #pragma unroll
