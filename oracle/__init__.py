@@ -84,6 +84,9 @@ def lib():
         L.ppow_oracle_adaw_sequence.restype = ctypes.c_int
         L.ppow_oracle_sample_starts.argtypes = [_c_double_p, i64, i64, _c_double_p, _c_int64_p]
         L.ppow_oracle_sample_starts.restype = ctypes.c_int
+        L.ppow_oracle_sample_starts_curriculum.argtypes = [_c_double_p, i64, i64, _c_double_p,
+                                                           _c_double_p, d, _c_int64_p]
+        L.ppow_oracle_sample_starts_curriculum.restype = ctypes.c_int
         L.ppow_oracle_select_windows.argtypes = [_c_double_p, i64, i64, _c_int64_p]
         L.ppow_oracle_select_windows.restype = ctypes.c_int
         _lib = L
@@ -282,6 +285,23 @@ def sample_starts(score, uniforms):
                                          out.ctypes.data_as(_c_int64_p))
     if rc != 0:
         raise ValueError("ppow_oracle_sample_starts rejected its arguments")
+    return out
+
+
+def sample_starts_curriculum(score, uniforms, mix_uniforms, adaw_fraction):
+    """Window starts under the hard-window curriculum: ADAW-selected (proportional to the
+    scores) where mix_uniforms < adaw_fraction, uniformly random otherwise."""
+    s = _f64(score)
+    if s.ndim != 2:
+        raise ValueError("score must be [N, W]")
+    u = _f64(uniforms).reshape(-1)
+    m = _f64(mix_uniforms).reshape(-1)
+    out = np.empty(s.shape[0], dtype=np.int64)
+    rc = lib().ppow_oracle_sample_starts_curriculum(_dp(s), s.shape[0], s.shape[1], _dp(u), _dp(m),
+                                                    float(adaw_fraction),
+                                                    out.ctypes.data_as(_c_int64_p))
+    if rc != 0:
+        raise ValueError("ppow_oracle_sample_starts_curriculum rejected its arguments")
     return out
 
 

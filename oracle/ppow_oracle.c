@@ -356,6 +356,26 @@ int ppow_oracle_sample_starts(const double *score, int64_t N, int64_t W, const d
     return 0;
 }
 
+int ppow_oracle_sample_starts_curriculum(const double *score, int64_t N, int64_t W,
+                                         const double *uniforms, const double *mix_uniforms,
+                                         double adaw_fraction, int64_t *start)
+{
+    if (!score || !uniforms || !mix_uniforms || !start || N < 0 || W < 1) return -1;
+    if (!(adaw_fraction >= 0.0 && adaw_fraction <= 1.0)) return -1;
+    for (int64_t n = 0; n < N; ++n) {
+        if (mix_uniforms[n] < adaw_fraction) {
+            /* an ADAW-selected window: proportional to the window scores */
+            if (ppow_oracle_sample_starts(score + n * W, 1, W, uniforms + n, start + n) != 0)
+                return -1;
+        } else {
+            /* an ordinary window: every start equally likely */
+            int64_t j = (int64_t)floor(uniforms[n] * (double)W);
+            start[n] = j < W - 1 ? j : W - 1;
+        }
+    }
+    return 0;
+}
+
 typedef struct {
     double score;
     int64_t index;

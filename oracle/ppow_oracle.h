@@ -161,6 +161,18 @@ int ppow_oracle_sample_starts(const double *score, int64_t N, int64_t W, const d
                               int64_t *start);
 
 /*
+ * Window starts under the hard-window curriculum (Appendix A.3, Table 5: the proportion of
+ * ADAW-selected windows grows 0.2 / 0.4 / 0.6 over training): sequence n gets an ADAW-selected
+ * start -- ppow_oracle_sample_starts with uniforms[n] -- when mix_uniforms[n] < adaw_fraction,
+ * and otherwise an ordinary window, every start equally likely: floor(uniforms[n] * W), capped
+ * at W-1.  (The paper does not say how the remaining windows are chosen; uniform starts are
+ * this build's reading.)  adaw_fraction in [0, 1]; returns 0 or -1.
+ */
+int ppow_oracle_sample_starts_curriculum(const double *score, int64_t N, int64_t W,
+                                         const double *uniforms, const double *mix_uniforms,
+                                         double adaw_fraction, int64_t *start);
+
+/*
  * Top-M selection: the M windows with the largest score, ordered by score
  * descending and, among equal scores, by index ascending (a full stable sort,
  * first M kept).  Section 4.2: windows with larger s_j are prioritised.

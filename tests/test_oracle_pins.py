@@ -428,3 +428,28 @@ def test_sample_starts_inverts_the_cumulative_distribution():
     picks = oracle.sample_starts(np.repeat(s[:1], u.size, 0), u)
     freq = np.bincount(picks, minlength=5) / u.size
     np.testing.assert_allclose(freq, s[0] / s[0].sum(), atol=2e-4)
+
+
+def test_curriculum_mixes_adaw_and_uniform_starts_in_the_stated_proportion():
+    """Hard-window curriculum (Appendix A.3, Table 5): a fraction rho of the windows is
+    ADAW-selected, the rest ordinary.  Over a grid of both draws the start frequencies must be
+    rho * s_j / sum(s) + (1 - rho) / W; rho = 1 is plain proportional sampling, rho = 0 plain
+    uniform sampling."""
+    s = np.array([[1.0, 0.0, 3.0, 0.0, 4.0]])
+    W = s.shape[1]
+    g = 400
+    u_start, u_mix = np.meshgrid((np.arange(g) + 0.5) / g, (np.arange(g) + 0.5) / g)
+    u_start, u_mix = u_start.ravel(), u_mix.ravel()
+    rows = np.repeat(s, u_start.size, 0)
+    for rho in (0.2, 0.4, 0.6):                              # Table 5's schedule
+        picks = oracle.sample_starts_curriculum(rows, u_start, u_mix, rho)
+        freq = np.bincount(picks, minlength=W) / picks.size
+        np.testing.assert_allclose(freq, rho * s[0] / s[0].sum() + (1 - rho) / W, atol=3e-3)
+    # a mistake in the direction of the comparison would swap the two shares
+    assert abs(freq[1] - 0.4 / W) < 3e-3 and abs(freq[4] - (0.6 * 0.5 + 0.4 / W)) < 3e-3
+    only_adaw = oracle.sample_starts_curriculum(rows, u_start, u_mix, 1.0)
+    assert np.array_equal(only_adaw, oracle.sample_starts(rows, u_start))
+    only_uniform = oracle.sample_starts_curriculum(rows, u_start, u_mix, 0.0)
+    assert np.array_equal(only_uniform, np.minimum(np.floor(u_start * W), W - 1).astype(np.int64))
+    with pytest.raises(ValueError):
+        oracle.sample_starts_curriculum(rows[:1], [0.5], [0.5], 1.5)
