@@ -28,8 +28,9 @@ HEADLINE = "rejection_bf16_128k"
 # the other workloads of the benchmark, reported in "configs" (the tiny fp32 case is a
 # parity-test case only: its whole input is 1 MB)
 OTHERS = ["greedy_bf16_32k", "twopass_f32_152k", "stream_bf16_128k", "sequence_bf16_128k"]
-RTOL = {"f32": 1e-4, "bf16": 2e-3}
+RTOL = {"f32": 1e-4, "bf16": 1e-4}     # the parity tests' bound (bf16 inputs held to the fp32 one)
 ATOL = 1e-6
+ATOL_DIVERGENCE = 4e-6                  # floor for divergences: two log-sum-exps cancel
 
 
 def parse_args():
@@ -105,9 +106,9 @@ def cpu_baseline(w, inputs, gpu_out, seconds, single_thread_windows):
     k_gpu = gpu_out.accepted_len[:n].cpu().numpy()
     rp_gpu = gpu_out.r_proximity[:n].cpu().numpy().astype(np.float64)
     errors = {"r_speedup": needed_rtol(gpu_out.r_speedup[:n].cpu(), res.r_speedup),
-              "adaw_score": needed_rtol(gpu_out.adaw_score[:n].cpu(), res.adaw_score),
+              "adaw_score": needed_rtol(gpu_out.adaw_score[:n].cpu(), res.adaw_score, ATOL_DIVERGENCE),
               "delta": needed_rtol(gpu_out.delta[:n].cpu(), res.delta, ATOL * math.log(w.V)),
-              "kl": needed_rtol(gpu_out.kl[:n].cpu(), res.kl),
+              "kl": needed_rtol(gpu_out.kl[:n].cpu(), res.kl, ATOL_DIVERGENCE),
               "confidence": needed_rtol(gpu_out.confidence[:n].cpu(), res.confidence),
               "accept_prob": needed_rtol(gpu_out.accept_prob[:n].cpu(), res.accept_prob)}
     if w.expected_accept:
@@ -117,9 +118,10 @@ def cpu_baseline(w, inputs, gpu_out, seconds, single_thread_windows):
         np.array_equal(k_gpu, res.accepted_len) and np.array_equal(rp_gpu, res.r_proximity)
         and all(e <= rtol for e in errors.values()))
     out["max_rel_error"] = errors
-    out["max_rel_error_note"] = ("per output, the relative tolerance |gpu - oracle| <= rtol*|oracle| + "
-                                 "1e-6 (x ln V for delta) would have needed on the sample; "
-                                 f"the bound is {rtol:g}; accepted_len and r_proximity are exact")
+    out["max_rel_error_note"] = ("per output, the rtol that |gpu - oracle| <= rtol*|oracle| + atol would "
+                                 "have needed on the sample (atol 1e-6, x ln V for delta, 4e-6 for kl "
+                                 f"and adaw_score); the bound is {rtol:g}; accepted_len and r_proximity "
+                                 "are exact")
     return out
 
 
@@ -195,8 +197,8 @@ def bench_sequences(args, w, dev, cpu_seconds):
         v_ref, s_ref = oracle.adaw_sequence(d["draft_logits"][:n].cpu(), d["target_logits"][:n].cpu(), K)
         picks = oracle.sample_starts(s_ref, d["uniforms"][:n].cpu().numpy().astype(np.float64))
         dt = time.perf_counter() - t0
-        errors = {"criticality": needed_rtol(buf.criticality[:n].cpu(), v_ref),
-                  "window_score": needed_rtol(buf.window_score[:n].cpu(), s_ref)}
+        errors = {"criticality": needed_rtol(buf.criticality[:n].cpu(), v_ref, ATOL_DIVERGENCE),
+                  "window_score": needed_rtol(buf.window_score[:n].cpu(), s_ref, ATOL_DIVERGENCE)}
         rtol = RTOL[w.dtype]
         # the start is drawn from fp32 scores on the GPU: compare with the oracle's draw on those
         s_gpu = buf.window_score[:n].cpu().numpy().astype(np.float64)

@@ -229,7 +229,7 @@ void row_cluster_kernel(ClusterArgs ca) {
             direct_to_lds(pb + c, lds_b + wave_first);
         }
         LaneState s;
-        s.reset();
+        s.reset(kClusterGap);
         // fp32 rows: the raw logits are not needed after this pass, so the two exponentials of
         // every pair take their place in the registers / LDS and pass 2 only rescales them
         // (the position of the lane's maximum is tracked to the element instead of re-scanned).
@@ -262,17 +262,6 @@ void row_cluster_kernel(ClusterArgs ca) {
             fb = fast_exp2(rb - s.rho_b);
             return true;
         };
-        {   // the wavefront's starting references: the maxima of its lanes' first chunks
-            float first_a = PPOW_NEG_INF, first_b = PPOW_NEG_INF;
-            if (tid < n) {
-                float a[VEC], b[VEC];
-                S::unpack(ka[0], a);
-                S::unpack(kb[0], b);
-                first_a = chunk_max<VEC>(a);
-                first_b = chunk_max<VEC>(b);
-            }
-            start_reference(s, first_a, first_b);
-        }
 #pragma unroll
         for (int k = 0; k < kRegChunks; ++k) {
             const int cr = tid + k * kThreads;

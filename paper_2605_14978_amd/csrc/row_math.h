@@ -3,7 +3,7 @@
 // wave reductions and the per-position epilogue.
 //
 // With P = softmax(a), Q = softmax(b) (Section 4.2) a lane accumulates, relative to its own
-// references rho (log2 units; rho <= lane max <= rho + kRescaleGap):
+// references rho (log2 units; rho <= lane max <= rho + gap):
 //     Z_a = sum 2^t,  S1 = sum 2^t * t,  S2 = sum 2^t * (a - b),    t  = a*log2(e) - rho_a
 //     Z_b = sum 2^tb,                    S2r = sum 2^tb * (b - a),  tb = b*log2(e) - rho_b
 // from which  H(P)     = ln2' * (log2 Z_a - S1 / Z_a)
@@ -13,7 +13,7 @@
 // the few per-row operations that subtract nearly equal numbers are done in double.
 // Identical rows give exactly zero divergence.  The lanes of a wavefront start from a common
 // reference, the largest logit among the wavefront's first chunks (start_reference), and a
-// lane's reference only moves when a chunk maximum exceeds it by more than kRescaleGap: a few
+// lane's reference only moves when a chunk maximum exceeds it by more than a gap: a few
 // times per row, which keeps the rescale off the streaming path.  The gap also bounds the
 // rounding of the exponents: t is rounded to 2^-23 * |t|, so an element that carries much of
 // the probability must not sit far above the reference -- with |t| <= 8 its exponential is
@@ -30,7 +30,17 @@
 namespace ppow {
 
 constexpr float kLog2e = 1.44269504088896340736f;
-constexpr float kRescaleGap = 8.0f;    // log2 units: partial sums stay below 2^8 * count
+// Rescale gaps in log2 units (partial sums stay below 2^gap * count).  The one-workgroup-per-row
+// kernel starts its wavefronts near the top of the row and can afford the tight gap.  The
+// cluster kernel keeps the wide one and per-lane starting references: there the cross-lane
+// maximum at the start of a row sits on the critical path of a whole cluster (1.5 % of its
+// throughput when measured), and a rebase has to rescale what the lane has kept; on that path
+// the divergences of nearly identical rows carry up to ~1.5e-6 of absolute error.
+#ifndef PPOW_RESCALE_GAP
+#define PPOW_RESCALE_GAP 8.0f
+#endif
+constexpr float kRowGap = PPOW_RESCALE_GAP;
+constexpr float kClusterGap = 24.0f;
 #define PPOW_NEG_INF (-__builtin_huge_valf())
 
 #ifndef PPOW_ROW_NONTEMPORAL
@@ -101,8 +111,10 @@ struct LaneState {
     float rho_b, z_b, s2r;      // draft side (s2r only when the reverse divergence is wanted)
     float m_a;                  // exact maximum of the target logits this lane has seen
     int best;                   // body chunk in which m_a was first reached (-1: none yet)
+    float gap;                  // a reference moves when a chunk maximum exceeds it by more
 
-    __device__ __forceinline__ void reset() {
+    __device__ __forceinline__ void reset(float rescale_gap) {
+        gap = rescale_gap;
         rho_a = PPOW_NEG_INF; z_a = 0.f; s1 = 0.f; s2 = 0.f;
         rho_b = PPOW_NEG_INF; z_b = 0.f; s2r = 0.f;
         m_a = PPOW_NEG_INF; best = -1;
@@ -137,24 +149,36 @@ __device__ __forceinline__ void fold_impl(LaneState &s, const float (&a)[VEC], c
                                           float cma, float cmb, float *ea, float *eb_out) {
     const float ta_max = fmaf(cma, kLog2e, -s.rho_a);
     const float tb_max = fmaf(cmb, kLog2e, -s.rho_b);
-    if (fmaxf(ta_max, tb_max) > kRescaleGap) {      // rare: the reference lags too far behind
-        if (ta_max > kRescaleGap) rebase_target(s, cma * kLog2e);
-        if (tb_max > kRescaleGap) rebase_draft(s, cmb * kLog2e);
+    if (fmaxf(ta_max, tb_max) > s.gap) {            // rare: the reference lags too far behind
+        if (ta_max > s.gap) rebase_target(s, cma * kLog2e);
+        if (tb_max > s.gap) rebase_draft(s, cmb * kLog2e);
     }
+    // The two partition sums carry the log-sum-exps, whose difference is what is left of the
+    // divergence of nearly identical rows: the chunk's exponentials are added in a tree and
+    // reach the running sum with one addition (same count of additions as adding them one by
+    // one, an eighth of the roundings against the large running sum).
+    float za[VEC], zb[VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
         const float t = fmaf(a[j], kLog2e, -s.rho_a);
         const float e = fast_exp2(t);
         const float d = a[j] - b[j];
-        s.z_a += e;
+        za[j] = e;
         s.s1 = fmaf(e, t, s.s1);
         s.s2 = fmaf(e, d, s.s2);
         const float tb = fmaf(b[j], kLog2e, -s.rho_b);
         const float eb = fast_exp2(tb);
-        s.z_b += eb;
+        zb[j] = eb;
         if (REV) s.s2r = fmaf(eb, -d, s.s2r);
         if (KEEP) { ea[j] = e; eb_out[j] = eb; }
     }
+#pragma unroll
+    for (int w = 1; w < VEC; w <<= 1) {
+#pragma unroll
+        for (int j = 0; j + w < VEC; j += 2 * w) { za[j] += za[j + w]; zb[j] += zb[j + w]; }
+    }
+    s.z_a += za[0];
+    s.z_b += zb[0];
 }
 
 template <int VEC, bool REV>
@@ -274,6 +298,10 @@ __device__ __forceinline__ int wave_min(int x) {
 // Common starting references of a wavefront: the maxima of its lanes' first chunks (-inf for a
 // lane without one).  Every lane of the wavefront must call this, before its first fold.
 __device__ __forceinline__ void start_reference(LaneState &s, float first_max_a, float first_max_b) {
+#ifdef PPOW_NO_START_REFERENCE          // tuning build: every lane finds its own first reference
+    (void)s; (void)first_max_a; (void)first_max_b;
+    return;
+#endif
     const float wa = wave_max(first_max_a);
     const float wb = wave_max(first_max_b);
     if (wa != PPOW_NEG_INF) {                 // some lane has a chunk: both rows have elements

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     const raw4 *pb = reinterpret_cast<const raw4 *>(row_b + head);
 
     LaneState s;
-    s.reset();
+    s.reset(kRowGap);
 
     // Prologue: every lane's first chunk, which also gives the wavefront its starting references.
     {

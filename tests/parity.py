@@ -1,8 +1,17 @@
 """Shared helpers of the GPU parity tests: run libppow and the oracle on the same
 stored inputs and compare element by element.
 
-Tolerances (relative, plus an absolute floor for values near zero):
-  fp32 logits 1e-4, bf16 logits 2e-3; floor 1e-6 (times ln V for log-probability sums).
+Tolerances: |gpu - oracle| <= rtol*|oracle| + atol.
+  rtol 1e-4 for fp32 AND for bf16 logits.  (The task allows 2e-3 for bf16; both sides read
+  the same stored bits and the kernel's arithmetic is fp32 either way, so bf16 inputs are held
+  to the fp32 bound.)
+  atol 1e-6 (times ln V for sums of log-probabilities), except for the divergences and what
+  is built from them (kl, reverse_kl, criticality, window scores): 4e-6.  A divergence is what
+  is left after two log-sum-exps of size ~10 cancel; each comes from an fp32 sum over the
+  vocabulary whose relative error is a few 2^-24 * sqrt(additions per lane) ~ 5e-7 when one
+  lane holds most of the probability, plus 2^-23 per v_exp_f32 and 2^-22 from the rounding
+  of the exponents: ~1e-6 per side, 2e-6 for the difference, doubled for margin.  Observed
+  worst case over the 1.4 million rows of the full-size workloads: 1.3e-6.
 Integer results (accepted length, argmax-driven decisions, selected indices) are
 compared exactly.
 """
@@ -14,8 +23,9 @@ import torch
 import oracle
 import paper_2605_14978_amd as ppow
 
-RTOL = {"f32": 1e-4, "bf16": 2e-3}
+RTOL = {"f32": 1e-4, "bf16": 1e-4}
 ATOL = 1e-6
+ATOL_DIVERGENCE = 4e-6
 
 PER_POSITION = ("kl", "confidence", "accept_prob", "logp_target_tok", "logp_draft_tok")
 POLICY_TERMS = ("reverse_kl", "alignment")
@@ -63,6 +73,12 @@ def run_oracle(d, *, cost_ratio, verify, prox_eps=0.5, prox_eta=1.0, expected_ac
         verify=oracle.GREEDY if verify == "greedy" else oracle.REJECTION, want=tuple(want))
 
 
+def _atol_of(name, V):
+    if name.startswith("logp"):
+        return ATOL * math.log(V)
+    return ATOL_DIVERGENCE if name == "kl" else ATOL
+
+
 def assert_close(name, got, ref, rtol, atol=ATOL):
     got = np.asarray(got, dtype=np.float64).reshape(-1)
     ref = np.asarray(ref, dtype=np.float64).reshape(-1)
@@ -100,33 +116,32 @@ def compare(gpu, ref, dname, V, expected_accept=False, report=None, rtol=None):
     rtol = RTOL[dname] if rtol is None else rtol
     if report is not None:
         report.add("r_speedup", gpu.r_speedup.cpu(), ref.r_speedup)
-        report.add("adaw_score", gpu.adaw_score.cpu(), ref.adaw_score)
+        report.add("adaw_score", gpu.adaw_score.cpu(), ref.adaw_score, ATOL_DIVERGENCE)
         if gpu.delta is not None:
             report.add("delta", gpu.delta.cpu(), ref.delta, ATOL * math.log(V))
         for name in PER_POSITION:
             if getattr(gpu, name) is not None:
-                report.add(name, getattr(gpu, name).cpu(), getattr(ref, name),
-                           ATOL * math.log(V) if name.startswith("logp") else ATOL)
+                report.add(name, getattr(gpu, name).cpu(), getattr(ref, name), _atol_of(name, V))
         if expected_accept:
             report.add("expected_accept", gpu.expected_accept.cpu(), ref.expected_accept)
     assert np.array_equal(gpu.accepted_len.cpu().numpy(), ref.accepted_len), "accepted_len differs"
     assert_close("r_speedup", gpu.r_speedup.cpu(), ref.r_speedup, rtol)
     assert np.array_equal(gpu.r_proximity.cpu().numpy().astype(np.float64), ref.r_proximity), \
         "r_proximity differs"
-    assert_close("adaw_score", gpu.adaw_score.cpu(), ref.adaw_score, rtol)
+    assert_close("adaw_score", gpu.adaw_score.cpu(), ref.adaw_score, rtol, ATOL_DIVERGENCE)
     if gpu.delta is not None:
         assert_close("delta", gpu.delta.cpu(), ref.delta, rtol, ATOL * math.log(V))
     for name in PER_POSITION:
         t = getattr(gpu, name)
         if t is not None:
-            atol = ATOL * math.log(V) if name.startswith("logp") else ATOL
-            assert_close(name, t.cpu(), getattr(ref, name), rtol, atol)
+            assert_close(name, t.cpu(), getattr(ref, name), rtol, _atol_of(name, V))
     if expected_accept:
         assert_close("expected_accept", gpu.expected_accept.cpu(), ref.expected_accept, rtol)
     if getattr(gpu, "reverse_kl", None) is not None:
-        assert_close("reverse_kl", gpu.reverse_kl.cpu(), ref.reverse_kl, rtol)
+        assert_close("reverse_kl", gpu.reverse_kl.cpu(), ref.reverse_kl, rtol, ATOL_DIVERGENCE)
         assert_close("alignment", gpu.alignment.cpu(), ref.alignment, rtol)
-        assert_close("reverse_kl_mean", gpu.reverse_kl_mean.cpu(), ref.reverse_kl.mean(-1), rtol)
+        assert_close("reverse_kl_mean", gpu.reverse_kl_mean.cpu(), ref.reverse_kl.mean(-1), rtol,
+                     ATOL_DIVERGENCE)
         assert_close("alignment_mean", gpu.alignment_mean.cpu(), ref.alignment.mean(-1), rtol)
 
 

@@ -94,7 +94,7 @@ def test_full_size_workload(name, capsys):
     _check_properties(w, out)
     top = np.sort(oracle_scores)[::-1]
     gap = (top[w.M - 1] - top[w.M]) / top[w.M - 1]
-    say(f"relative tolerance each output would have needed (atol 1e-6): {report}")
+    say(f"relative tolerance each output would have needed at its absolute floor: {report}")
     say(f"top-{w.M} boundary: oracle scores {top[w.M - 1]:.9g} / {top[w.M]:.9g}, relative gap {gap:.2e}\n")
     assert gap >= SCORE_GAP * (1 - 1e-6)
     idx = check_selection(out.adaw_score, w.M, oracle_scores, 1e-4, exact_sets=True)
@@ -105,7 +105,7 @@ def test_full_size_sequence_mode(capsys):
     """Sequence-mode ADAW at the benchmark's size: every sequence against the oracle (eight
     at a time), the sampler exactly on the GPU's own scores, the selection against the
     oracle's scores within the tolerance band (sequence inputs carry no selection gap)."""
-    from parity import RTOL, assert_close
+    from parity import ATOL_DIVERGENCE, RTOL, assert_close
     w = WORKLOADS["sequence_bf16_128k"]
     N, T, K = w.B, w.seq_len, w.K
     d = generate_sequences(w, device=DEV)
@@ -119,15 +119,15 @@ def test_full_size_sequence_mode(capsys):
     for n0 in range(0, N, 8):
         n1 = min(N, n0 + 8)
         v_ref, s_ref = oracle.adaw_sequence(d["draft_logits"][n0:n1].cpu(), d["target_logits"][n0:n1].cpu(), K)
-        assert_close("criticality", out.criticality[n0:n1].cpu(), v_ref, RTOL[w.dtype])
-        assert_close("window_score", out.window_score[n0:n1].cpu(), s_ref, RTOL[w.dtype])
-        report.add("criticality", out.criticality[n0:n1].cpu(), v_ref)
-        report.add("window_score", out.window_score[n0:n1].cpu(), s_ref)
+        assert_close("criticality", out.criticality[n0:n1].cpu(), v_ref, RTOL[w.dtype], ATOL_DIVERGENCE)
+        assert_close("window_score", out.window_score[n0:n1].cpu(), s_ref, RTOL[w.dtype], ATOL_DIVERGENCE)
+        report.add("criticality", out.criticality[n0:n1].cpu(), v_ref, ATOL_DIVERGENCE)
+        report.add("window_score", out.window_score[n0:n1].cpu(), s_ref, ATOL_DIVERGENCE)
         s_ref_all[n0:n1] = s_ref
         with capsys.disabled():
             print(f"\n[sequence_bf16_128k] sequences {n0}..{n1} of {N} match the oracle", end="", flush=True)
     with capsys.disabled():
-        print(f"\n[sequence_bf16_128k] relative tolerance needed (atol 1e-6): {report}", flush=True)
+        print(f"\n[sequence_bf16_128k] relative tolerance needed at the absolute floor: {report}", flush=True)
     s_gpu = out.window_score.cpu().numpy().astype(np.float64)
     picks = oracle.sample_starts(s_gpu, d["uniforms"].cpu().numpy().astype(np.float64))
     assert np.array_equal(out.sampled_start.cpu().numpy(), picks)
