@@ -159,12 +159,20 @@ size_t ppow_adaw_sequence_workspace_bytes(int64_t N, int32_t T, int64_t V, int32
  * position belongs to up to K overlapping windows), then
  *   criticality[n, t]  = C(P_t) * KL(P_t || Q_t)                         t = 0..T-1
  *   window_score[n, j] = (1/K) sum_{t=j}^{j+K-1} criticality[n, t]       j = 0..T-K
- * and, if asked, one window start per sequence drawn with probability proportional to its
- * window scores: the smallest j whose cumulative score reaches uniforms[n] times the total
- * (running sums in double, index order; if all scores are zero, floor(u * (T-K+1))).
+ * and, if asked, one window start per sequence.  Under the hard-window curriculum
+ * (Appendix A.3, Table 5: the proportion of ADAW-selected windows grows 0.2 / 0.4 / 0.6 over
+ * training) sequence n gets an ADAW-selected start when mix_uniforms[n] < adaw_fraction and
+ * an ordinary one, floor(uniforms[n] * (T-K+1)), otherwise (how the other windows are chosen
+ * the paper does not say: uniformly random is this library's reading).  An ADAW-selected start
+ * is drawn with probability proportional to the window scores: the smallest j whose cumulative
+ * score reaches uniforms[n] times the total (running sums in double; if all scores are zero,
+ * floor(u * (T-K+1))).
  *
  *   draft_logits, target_logits  [N, T, V] as in ppow_score_windows
  *   uniforms       [N] float32 in [0,1), required iff sampled_start is given
+ *   adaw_fraction  in [0, 1]; 1 = every start ADAW-selected (Algorithm 1 as printed)
+ *   mix_uniforms   [N] float32 in [0,1), required iff sampled_start is given and
+ *                  adaw_fraction < 1
  *   criticality    [N*T] out or NULL;  window_score [N*(T-K+1)] out, required
  *   sampled_start  [N] int32 out or NULL
  *   N >= 0, 1 <= K <= T, N*T < 2^31, 2 <= V < 2^31.
@@ -172,8 +180,8 @@ size_t ppow_adaw_sequence_workspace_bytes(int64_t N, int32_t T, int64_t V, int32
  */
 int ppow_adaw_sequence(const void *draft_logits, const void *target_logits,
                        int64_t N, int32_t T, int64_t V, int32_t dtype, int32_t K,
-                       const float *uniforms, float *criticality, float *window_score,
-                       int32_t *sampled_start,
+                       const float *uniforms, float adaw_fraction, const float *mix_uniforms,
+                       float *criticality, float *window_score, int32_t *sampled_start,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Bytes of device workspace ppow_select_windows needs (0 on invalid sizes). */

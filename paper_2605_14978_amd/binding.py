@@ -81,7 +81,8 @@ def lib():
         L.ppow_debug_cluster_wait_limit.restype = None
         L.ppow_adaw_sequence_workspace_bytes.argtypes = [i64, i32, i64, i32]
         L.ppow_adaw_sequence_workspace_bytes.restype = sz
-        L.ppow_adaw_sequence.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.ppow_adaw_sequence.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, ctypes.c_float, vp,
+                                         vp, vp, vp, vp, sz, vp]
         L.ppow_adaw_sequence.restype = ctypes.c_int
         L.ppow_select_workspace_bytes.argtypes = [i64, i32]
         L.ppow_select_workspace_bytes.restype = sz
@@ -257,11 +258,14 @@ class SequenceBuffers:
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
 
-def ppow_adaw_sequence(draft_logits, target_logits, K, uniforms=None, *, buffers=None, stream=None):
+def ppow_adaw_sequence(draft_logits, target_logits, K, uniforms=None, *, adaw_fraction=1.0,
+                       mix_uniforms=None, buffers=None, stream=None):
     """Sequence-mode ADAW on [N, T, V] teacher-forced logits; returns the SequenceBuffers.
 
-    With `uniforms` ([N] float32) one window start per sequence is drawn in proportion to
-    the window scores.  Asynchronous on `stream` (default: torch's current stream).
+    With `uniforms` ([N] float32) one window start per sequence is drawn: in proportion to
+    the window scores where mix_uniforms[n] < adaw_fraction (always, for adaw_fraction = 1),
+    uniformly otherwise (hard-window curriculum).  Asynchronous on `stream` (default: torch's
+    current stream).
     """
     if not target_logits.is_cuda:
         raise RuntimeError("libppow scores device tensors only; there is no CPU path")
@@ -270,14 +274,15 @@ def ppow_adaw_sequence(draft_logits, target_logits, K, uniforms=None, *, buffers
         raise ValueError("draft and target logits must share shape and dtype")
     if not (draft_logits.is_contiguous() and target_logits.is_contiguous()):
         raise ValueError("logits must be contiguous")
-    if uniforms is not None and (uniforms.dtype != torch.float32 or uniforms.numel() != N
-                                 or not uniforms.is_contiguous()):
-        raise ValueError("uniforms must be contiguous float32 [N]")
+    for name, t in (("uniforms", uniforms), ("mix_uniforms", mix_uniforms)):
+        if t is not None and (t.dtype != torch.float32 or t.numel() != N or not t.is_contiguous()):
+            raise ValueError(f"{name} must be contiguous float32 [N]")
     code = _dtype_code(target_logits)
     if buffers is None:
         buffers = SequenceBuffers(N, T, V, K, code, target_logits.device, sample=uniforms is not None)
     _check(lib().ppow_adaw_sequence(
         _ptr(draft_logits), _ptr(target_logits), N, T, V, code, int(K), _ptr(uniforms),
+        float(adaw_fraction), _ptr(mix_uniforms),
         _ptr(buffers.criticality), _ptr(buffers.window_score),
         _ptr(buffers.sampled_start) if uniforms is not None else None,
         _ptr(buffers.workspace), buffers.workspace.numel(), _stream_handle(stream)))

@@ -35,7 +35,7 @@ extern "C" {
 
 const char *ppow_last_error(void) { return g_error; }
 
-const char *ppow_version(void) { return "0.2.0"; }
+const char *ppow_version(void) { return "0.3.0"; }
 
 const char *ppow_last_row_kernel(void) { return g_row_kernel; }
 
@@ -228,6 +228,7 @@ size_t ppow_adaw_sequence_workspace_bytes(int64_t N, int32_t T, int64_t V, int32
 
 int ppow_adaw_sequence(const void *draft_logits, const void *target_logits, int64_t N, int32_t T,
                        int64_t V, int32_t dtype, int32_t K, const float *uniforms,
+                       float adaw_fraction, const float *mix_uniforms,
                        float *criticality, float *window_score, int32_t *sampled_start,
                        void *workspace, size_t workspace_bytes, void *hip_stream) {
     const size_t need = ppow_adaw_sequence_workspace_bytes(N, T, V, dtype);
@@ -243,6 +244,10 @@ int ppow_adaw_sequence(const void *draft_logits, const void *target_logits, int6
         return fail(PPOW_ERR_INVALID_ARG, "logit base pointers must be 16-byte aligned");
     if (sampled_start && !uniforms)
         return fail(PPOW_ERR_INVALID_ARG, "sampled_start needs uniforms");
+    if (sampled_start && !(adaw_fraction >= 0.f && adaw_fraction <= 1.f))
+        return fail(PPOW_ERR_INVALID_ARG, "adaw_fraction must lie in [0, 1]");
+    if (sampled_start && adaw_fraction < 1.f && !mix_uniforms)
+        return fail(PPOW_ERR_INVALID_ARG, "an adaw_fraction below 1 needs mix_uniforms");
     if (!workspace || !aligned16(workspace) || workspace_bytes < need)
         return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
 
@@ -262,6 +267,8 @@ int ppow_adaw_sequence(const void *draft_logits, const void *target_logits, int6
     ppow::SequenceArgs sa;
     sa.records = ra.records;
     sa.uniforms = uniforms;
+    sa.mix_uniforms = adaw_fraction < 1.f ? mix_uniforms : nullptr;
+    sa.adaw_fraction = adaw_fraction;
     sa.criticality = criticality;
     sa.window_score = window_score;
     sa.sampled_start = sampled_start;

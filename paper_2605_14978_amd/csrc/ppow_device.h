@@ -76,6 +76,8 @@ struct GroupArgs {
 struct SequenceArgs {
     const RowRecord *records;    // [N*T]
     const float *uniforms;       // [N] or nullptr
+    const float *mix_uniforms;   // [N] curriculum draws, or nullptr: every start is ADAW-selected
+    float adaw_fraction;         // share of ADAW-selected starts (Appendix A.3)
     float *criticality;          // [N*T] or nullptr
     float *window_score;         // [N*(T-K+1)]
     int32_t *sampled_start;      // [N] or nullptr

@@ -125,14 +125,36 @@ __global__ __launch_bounds__(kThreads) void group_epilogue_kernel(GroupArgs args
 
 // Sequence-mode ADAW (Algorithm 1): one workgroup per sequence of T scored positions.
 //   window_score[j] = (1/K) sum_{t=j}^{j+K-1} v_t, summed in index order;
-//   sampled start: inverse of the cumulative distribution of the window scores at the given
-//   uniform draw, the running sum kept in double and in index order (so the decision is the
-//   one a double-precision reference takes on the same fp32 scores); all-zero scores fall
-//   back to a uniform draw floor(u * W).
-constexpr int kSeqLdsScores = 8192;        // window scores of one sequence staged in LDS (32 KB)
+//   sampled start: under the hard-window curriculum (Appendix A.3, Table 5) the window is an
+//   ADAW-selected one when the sequence's mixing draw is below the ADAW fraction, else an
+//   ordinary one, floor(u * W).  An ADAW-selected start inverts the cumulative distribution
+//   of the window scores at the draw u: the smallest j whose running sum reaches u times the
+//   total; all-zero scores fall back to floor(u * W).  The running sums are double: wavefront
+//   0 splits the scores into 64 contiguous segments, each lane adds up its own, a wavefront
+//   scan of the 64 segment sums gives every lane the sum before its segment, and the lane
+//   whose segment contains the crossing walks it again.  (A double sum of fp32 scores is
+//   exact or within 2^-53 of exact whatever its order, so the decision is the one an
+//   index-order double sum takes, up to draws within ~1e-16 of a boundary.)
+constexpr int kSeqLdsScores = 8192;        // window scores of one sequence staged in LDS
+__device__ __forceinline__ int padded(int j) { return j + (j >> 5); }   // segment starts in distinct banks
+
+__device__ __forceinline__ double shuffle_up(double x, int delta) {
+    const long long bits = __builtin_bit_cast(long long, x);
+    const int lo = __shfl_up(static_cast<int>(bits), delta, 64);
+    const int hi = __shfl_up(static_cast<int>(bits >> 32), delta, 64);
+    return __builtin_bit_cast(double, (static_cast<long long>(hi) << 32) |
+                                          static_cast<long long>(static_cast<unsigned>(lo)));
+}
+__device__ __forceinline__ double broadcast(double x, int lane) {
+    const long long bits = __builtin_bit_cast(long long, x);
+    const int lo = __shfl(static_cast<int>(bits), lane, 64);
+    const int hi = __shfl(static_cast<int>(bits >> 32), lane, 64);
+    return __builtin_bit_cast(double, (static_cast<long long>(hi) << 32) |
+                                          static_cast<long long>(static_cast<unsigned>(lo)));
+}
 
 __global__ __launch_bounds__(kThreads) void sequence_windows_kernel(SequenceArgs args) {
-    __shared__ float sh_score[kSeqLdsScores];
+    __shared__ float sh_score[kSeqLdsScores + kSeqLdsScores / 32 + 1];
     const int64_t n = blockIdx.x;
     const int T = args.T, K = args.K, W = T - K + 1;
     const RowRecord *rec = args.records + n * T;
@@ -144,55 +166,49 @@ __global__ __launch_bounds__(kThreads) void sequence_windows_kernel(SequenceArgs
         for (int t = 0; t < K; ++t) sum += rec[j + t].criticality;
         const float s = sum / static_cast<float>(K);
         score[j] = s;
-        if (j < kSeqLdsScores) sh_score[j] = s;
+        if (j < kSeqLdsScores) sh_score[padded(j)] = s;
     }
     if (!args.sampled_start) return;
     __syncthreads();                        // the scores of this sequence are all written
-    if (threadIdx.x == 0) {
-        // One lane walks the scores in index order with a double running sum: first the part
-        // staged in LDS, fetched eight at a time so that the additions, not the loads, set the
-        // pace, then whatever a very long sequence left in memory.
-        const int in_lds = W < kSeqLdsScores ? W : kSeqLdsScores;
-        double total = 0.0;
-        int j = 0;
-        for (; j + 8 <= in_lds; j += 8) {
-            float x[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = sh_score[j + i];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) total += static_cast<double>(x[i]);
-        }
-        for (; j < in_lds; ++j) total += static_cast<double>(sh_score[j]);
-        for (; j < W; ++j) total += static_cast<double>(score[j]);
-        const double u = static_cast<double>(args.uniforms[n]);
-        int pick = W - 1;
-        if (!(total > 0.0)) {
-            const int f = static_cast<int>(floor(u * static_cast<double>(W)));
-            pick = f < W - 1 ? f : W - 1;
-        } else {
-            const double threshold = u * total;
-            double c = 0.0;
-            int first = W;                    // first index whose running sum reaches the threshold
-            for (j = 0; j + 8 <= in_lds && first == W; j += 8) {
-                float x[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) x[i] = sh_score[j + i];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    c += static_cast<double>(x[i]);
-                    first = (first == W && c >= threshold) ? j + i : first;
-                }
-            }
-            if (first == W) {
-                for (; j < W; ++j) {
-                    c += static_cast<double>(j < kSeqLdsScores ? sh_score[j] : score[j]);
-                    if (c >= threshold) { first = j; break; }
-                }
-            }
-            pick = first < W ? first : W - 1;
-        }
-        args.sampled_start[n] = pick;
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x;
+    const double u = static_cast<double>(args.uniforms[n]);
+    const int uniform_pick = min(static_cast<int>(floor(u * static_cast<double>(W))), W - 1);
+    const bool adaw = !args.mix_uniforms || args.mix_uniforms[n] < args.adaw_fraction;
+    if (!adaw) {                            // uniform over the wavefront: an ordinary window
+        if (lane == 0) args.sampled_start[n] = uniform_pick;
+        return;
     }
+    auto score_at = [&](int j) { return j < kSeqLdsScores ? sh_score[padded(j)] : score[j]; };
+    const int per = (W + 63) / 64;          // lane l owns scores [l*per, min(W, (l+1)*per))
+    const int j0 = min(lane * per, W), j1 = min(j0 + per, W);
+    double mine = 0.0;
+    for (int j = j0; j < j1; ++j) mine += static_cast<double>(score_at(j));
+    double upto = mine;                     // inclusive scan over the lanes
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double prev = shuffle_up(upto, off);
+        if (lane >= off) upto += prev;
+    }
+    const double total = broadcast(upto, 63);
+    int pick = uniform_pick;                // all-zero scores: the weights are undefined
+    if (total > 0.0) {
+        const double threshold = u * total;
+        const unsigned long long reached = __ballot(upto >= threshold);
+        // first lane whose running sum reaches the threshold; rounding may leave none
+        const int owner = reached ? __builtin_ctzll(reached) : 63;
+        const double before = shuffle_up(upto, 1);      // sum of the scores before this segment
+        int first = j1 - 1;                 // if rounding leaves the walk short: the segment's end
+        if (lane == owner) {
+            double c = lane == 0 ? 0.0 : before;
+            for (int j = j0; j < j1; ++j) {
+                c += static_cast<double>(score_at(j));
+                if (c >= threshold) { first = j; break; }
+            }
+        }
+        pick = __shfl(first, owner, 64);
+    }
+    if (lane == 0) args.sampled_start[n] = pick;
 }
 
 }  // namespace

@@ -100,15 +100,18 @@ def test_sequence_argument_errors_return_before_any_launch():
     L = ppow.lib()
     E, W = binding.PPOW_ERR_INVALID_ARG, binding.PPOW_ERR_WORKSPACE
 
-    def seq(draft=16, target=32, N=2, T=8, V=100, dtype=0, K=4, u=None, crit=None, score=4096,
-            start=None, ws=4096, ws_bytes=1 << 24):
-        return L.ppow_adaw_sequence(draft, target, N, T, V, dtype, K, u, crit, score, start, ws,
-                                    ws_bytes, None)
+    def seq(draft=16, target=32, N=2, T=8, V=100, dtype=0, K=4, u=None, rho=1.0, mix=None, crit=None,
+            score=4096, start=None, ws=4096, ws_bytes=1 << 24):
+        return L.ppow_adaw_sequence(draft, target, N, T, V, dtype, K, u, rho, mix, crit, score, start,
+                                    ws, ws_bytes, None)
     assert L.ppow_adaw_sequence_workspace_bytes(64, 2048, 128256, 1) == (1 << 20) + 64 * 2048 * 32
     assert L.ppow_adaw_sequence_workspace_bytes(2, 0, 100, 0) == 0
     assert seq(K=0) == E and seq(K=9) == E and seq(T=0) == E and seq(V=1) == E and seq(dtype=3) == E
     assert seq(N=-1) == E and seq(draft=None) == E and seq(score=None) == E and seq(target=40) == E
     assert seq(start=4096) == E                      # sampling needs uniforms
+    assert seq(start=4096, u=8192, rho=0.4) == E     # a curriculum fraction below 1 needs its draws
+    assert seq(start=4096, u=8192, rho=1.5, mix=64) == E and seq(start=4096, u=8192, rho=-0.1, mix=64) == E
+    assert seq(start=4096, u=8192, rho=float("nan"), mix=64) == E
     assert seq(ws=None) == W and seq(ws_bytes=64) == W
     assert seq(N=0, draft=None, target=None, score=None) == binding.PPOW_OK
 
