@@ -29,7 +29,8 @@ extern "C" {
 typedef enum {
     PPOW_OK = 0,
     PPOW_ERR_INVALID_ARG = 1,  /* NULL required pointer, size or enum out of range */
-    PPOW_ERR_UNSUPPORTED = 2,  /* valid request outside the built limits           */
+    PPOW_ERR_UNSUPPORTED = 2,  /* valid request outside a built-in limit (the rows
+                                  ppow_score_windows_static holds)                 */
     PPOW_ERR_WORKSPACE = 3,    /* workspace NULL, misaligned or too small          */
     PPOW_ERR_DEVICE = 4        /* a HIP launch reported an error                   */
 } ppow_status;
@@ -149,6 +150,29 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
                        int64_t B, int32_t K, int64_t V, int32_t dtype,
                        const ppow_params *params, const ppow_outputs *out,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * ppow_score_windows for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, outputs, kernels and error behaviour as
+ * ppow_score_windows, minus the workspace: the records between the row kernel
+ * and the window epilogue live in an array built into the library
+ * (PPOW_STATIC_SCRATCH_BYTES of device memory per GPU the library is used on,
+ * held until the process ends).  B*K must not exceed PPOW_STATIC_MAX_ROWS
+ * (PPOW_ERR_UNSUPPORTED otherwise: use ppow_score_windows).  The call allocates
+ * and frees nothing; its first call on a device resolves the array's address
+ * and creates the event described at ppow_release().  All calls on one GPU share
+ * that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race and give undefined outputs -- order them yourself.
+ */
+#define PPOW_STATIC_MAX_ROWS 131072     /* B*K; 16384 windows of K = 8 */
+#define PPOW_STATIC_SCRATCH_BYTES ((1u << 20) + 32u * PPOW_STATIC_MAX_ROWS)   /* 5 MiB */
+int ppow_score_windows_static(const void *draft_logits, const void *target_logits,
+                              const int32_t *draft_tokens, const float *uniforms,
+                              const float *ref_logprob,
+                              int64_t B, int32_t K, int64_t V, int32_t dtype,
+                              const ppow_params *params, const ppow_outputs *out,
+                              void *hip_stream);
 
 /* Bytes of device workspace ppow_adaw_sequence needs (0 on invalid sizes). */
 size_t ppow_adaw_sequence_workspace_bytes(int64_t N, int32_t T, int64_t V, int32_t dtype);

@@ -27,6 +27,7 @@ PPOW_VERIFY_GREEDY = 1
 PPOW_FLAG_EXPECTED_ACCEPT = 1
 PPOW_FLAG_POLICY_TERMS = 2
 PPOW_MAX_K = 64
+PPOW_STATIC_MAX_ROWS = 131072
 
 _f32p = ctypes.POINTER(ctypes.c_float)
 _i32p = ctypes.POINTER(ctypes.c_int32)
@@ -75,6 +76,10 @@ def lib():
                                          ctypes.POINTER(PpowParams), ctypes.POINTER(PpowOutputs),
                                          vp, sz, vp]
         L.ppow_score_windows.restype = ctypes.c_int
+        L.ppow_score_windows_static.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32,
+                                                ctypes.POINTER(PpowParams),
+                                                ctypes.POINTER(PpowOutputs), vp]
+        L.ppow_score_windows_static.restype = ctypes.c_int
         L.ppow_release.argtypes = []
         L.ppow_release.restype = ctypes.c_int
         L.ppow_debug_cluster_wait_limit.argtypes = [u32]
@@ -240,6 +245,25 @@ def ppow_score_windows(draft_logits, target_logits, draft_tokens, uniforms=None,
         _ptr(draft_logits), _ptr(target_logits), _ptr(draft_tokens), _ptr(uniforms),
         _ptr(ref_logprob), B, K, V, code, ctypes.byref(params), ctypes.byref(outs),
         _ptr(buffers.workspace), buffers.workspace.numel(), _stream_handle(stream)))
+    return buffers
+
+
+def ppow_score_windows_static(draft_logits, target_logits, draft_tokens, uniforms=None,
+                              ref_logprob=None, *, cost_ratio, prox_eps=0.5, prox_eta=1.0,
+                              verify=PPOW_VERIFY_REJECTION, flags=0, rollout_group=0,
+                              adv_delta=1e-6, buffers, stream=None):
+    """ppow_score_windows without a workspace: the library's built-in scratch is used, nothing
+    is allocated by the call (`buffers` are the caller's preallocated outputs, e.g.
+    ScoreBuffers(..., workspace=False)).  B*K <= PPOW_STATIC_MAX_ROWS; calls that overlap on
+    one GPU race."""
+    B, K, V, code = _marshal_score(draft_logits, target_logits, draft_tokens, uniforms, ref_logprob)
+    params = PpowParams(float(cost_ratio), float(prox_eps), float(prox_eta), int(verify), int(flags),
+                        int(rollout_group), float(adv_delta))
+    outs = buffers.as_struct()
+    _check(lib().ppow_score_windows_static(
+        _ptr(draft_logits), _ptr(target_logits), _ptr(draft_tokens), _ptr(uniforms),
+        _ptr(ref_logprob), B, K, V, code, ctypes.byref(params), ctypes.byref(outs),
+        _stream_handle(stream)))
     return buffers
 
 

@@ -7,6 +7,18 @@
 
 #include <math.h>
 
+#include <mutex>
+
+// ---- scratch of the entry point that allocates nothing -----------------------------------
+// Same layout as the caller-supplied workspace of ppow_score_windows: the cluster kernel's
+// exchange words, then one record per (window, position).  Every device the library runs on
+// holds its own copy of the array, at its own address, until the process ends.  In host code
+// the name `scratch` is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kStaticScratchBytes =
+    ppow::kClusterScratchBytes + static_cast<size_t>(PPOW_STATIC_MAX_ROWS) * sizeof(ppow::RowRecord);
+static_assert(kStaticScratchBytes == PPOW_STATIC_SCRATCH_BYTES, "header states the size");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local char g_error[256] = "";
@@ -189,6 +201,46 @@ int enqueue_score(const void *draft_logits, const void *target_logits,
     return PPOW_OK;
 }
 
+struct StaticScratch {
+    std::mutex lock;
+    void *ptr[64] = {};        // device address of `scratch` on each device, once resolved
+};
+StaticScratch &static_scratch() {
+    static StaticScratch s;
+    return s;
+}
+
+// Device address of this device's copy of `scratch`.  The array's name is only a host-side
+// handle: the address comes from hipGetSymbolAddress, once per device, with that device
+// current; the same set-up creates the event that chains cluster launches, so that later
+// calls create nothing at all.
+int static_scratch_for_current_device(void **out_ptr) {
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess)
+        return fail(PPOW_ERR_DEVICE, "hipGetDevice failed: %s", hipGetErrorString(err));
+    if (dev < 0 || dev >= 64)
+        return fail(PPOW_ERR_UNSUPPORTED, "device ordinal %d is beyond the 64 the library tracks", dev);
+    StaticScratch &s = static_scratch();
+    std::lock_guard<std::mutex> guard(s.lock);
+    if (!s.ptr[dev]) {
+        void *p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(PPOW_ERR_DEVICE, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev,
+                        hipGetErrorString(err));
+        }
+        err = ppow::prepare_cluster_chain();
+        if (err != hipSuccess)
+            return fail(PPOW_ERR_DEVICE, "event creation failed on device %d: %s", dev,
+                        hipGetErrorString(err));
+        s.ptr[dev] = p;
+    }
+    *out_ptr = s.ptr[dev];
+    return PPOW_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -206,6 +258,25 @@ int ppow_score_windows(const void *draft_logits, const void *target_logits,
         return fail(PPOW_ERR_WORKSPACE, "workspace must be 16-byte aligned and hold %zu bytes", need);
     return enqueue_score(draft_logits, target_logits, draft_tokens, uniforms, ref_logprob, B, K, V,
                          dtype, params, out, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int ppow_score_windows_static(const void *draft_logits, const void *target_logits,
+                              const int32_t *draft_tokens, const float *uniforms,
+                              const float *ref_logprob, int64_t B, int32_t K, int64_t V,
+                              int32_t dtype, const ppow_params *params, const ppow_outputs *out,
+                              void *hip_stream) {
+    const int status = validate_score_args(draft_logits, target_logits, draft_tokens, uniforms, B, K,
+                                           V, dtype, params, out);
+    if (status != PPOW_OK || B == 0) return status;
+    if (B * K > PPOW_STATIC_MAX_ROWS)
+        return fail(PPOW_ERR_UNSUPPORTED,
+                    "B*K = %lld positions exceed the %d the built-in scratch holds; use "
+                    "ppow_score_windows with a workspace", (long long)(B * K), PPOW_STATIC_MAX_ROWS);
+    void *ptr = nullptr;
+    const int ready = static_scratch_for_current_device(&ptr);
+    if (ready != PPOW_OK) return ready;
+    return enqueue_score(draft_logits, target_logits, draft_tokens, uniforms, ref_logprob, B, K, V,
+                         dtype, params, out, ptr, static_cast<hipStream_t>(hip_stream));
 }
 
 int ppow_release(void) {

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported():
     assert {"ppow_score_windows", "ppow_select_windows", "ppow_score_workspace_bytes",
             "ppow_select_workspace_bytes", "ppow_last_error", "ppow_version",
             "ppow_last_row_kernel", "ppow_adaw_sequence",
-            "ppow_adaw_sequence_workspace_bytes", "ppow_release",
+            "ppow_adaw_sequence_workspace_bytes", "ppow_score_windows_static", "ppow_release",
             "ppow_debug_cluster_wait_limit"} <= set(names)
     L = ppow.lib()
     for name in names:
@@ -137,3 +137,21 @@ def test_binding_refuses_cpu_tensors():
     with pytest.raises(RuntimeError, match="no CPU path"):
         ppow.ppow_select_windows(torch.zeros(8), 2)
 
+
+def test_static_entry_point_rejects_on_the_host_what_it_can():
+    """Bad arguments and sizes beyond the built-in scratch are refused before any device call."""
+    L = ppow.lib()
+    p = binding.PpowParams(0.05, 0.5, 1.0, 0, 0, 0, 0.0)
+    o = binding.PpowOutputs(*([4096] * 4 + [None] * 14))
+
+    def call(B=4, K=2, V=100, draft=16, params=p):
+        return L.ppow_score_windows_static(draft, 32, 48, 64, None, B, K, V, 0,
+                                           ctypes.byref(params), ctypes.byref(o), None)
+
+    assert call(draft=None) == binding.PPOW_ERR_INVALID_ARG
+    assert call(K=65) == binding.PPOW_ERR_INVALID_ARG
+    assert call(params=binding.PpowParams(-1.0, 0.5, 1.0, 0, 0, 0, 0.0)) == binding.PPOW_ERR_INVALID_ARG
+    assert call(B=binding.PPOW_STATIC_MAX_ROWS // 2 + 1, K=2) == binding.PPOW_ERR_UNSUPPORTED
+    assert b"built-in scratch" in L.ppow_last_error()
+    assert call(B=0) == binding.PPOW_OK
+    assert L.ppow_release() == binding.PPOW_OK          # nothing held: a no-op
