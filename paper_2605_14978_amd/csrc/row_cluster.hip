@@ -146,7 +146,7 @@ __device__ __forceinline__ void close_row(const ClusterArgs &ca, const PendingCl
         }
     }
     const float expected = wave_sum(has ? value_of(w) : 0.f);
-    if (lane == 0) finish_row<DTYPE>(ca.row, p.row, p.totals, expected, p.drafted);
+    if (lane == 0) finish_row<DTYPE, ClusterFold>(ca.row, p.row, p.totals, expected, p.drafted);
 }
 
 template <int DTYPE, bool REV>
@@ -229,7 +229,7 @@ void row_cluster_kernel(ClusterArgs ca) {
             direct_to_lds(pb + c, lds_b + wave_first);
         }
         LaneState s;
-        s.reset(kClusterGap);
+        s.reset();
         // fp32 rows: the raw logits are not needed after this pass, so the two exponentials of
         // every pair take their place in the registers / LDS and pass 2 only rescales them
         // (the position of the lane's maximum is tracked to the element instead of re-scanned).
@@ -272,12 +272,12 @@ void row_cluster_kernel(ClusterArgs ca) {
                 if constexpr (KEEP) {
                     const float ra = s.rho_a, rb = s.rho_b;
                     float ea[VEC], eb[VEC], fa, fb;
-                    fold_chunk_keep<VEC, REV>(s, a, b, cr, first_elem, ea, eb);
+                    fold_chunk_keep<ClusterFold, VEC, REV>(s, a, b, cr, first_elem, ea, eb);
                     if (k > 0 && moved(ra, rb, fa, fb)) rescale_kept(k, 0, fa, fb);
                     ka[k] = S::pack(ea);
                     kb[k] = S::pack(eb);
                 } else {
-                    fold_chunk<VEC, REV>(s, a, b, cr);
+                    fold_chunk<ClusterFold, VEC, REV>(s, a, b, cr);
                 }
             }
         }
@@ -289,12 +289,12 @@ void row_cluster_kernel(ClusterArgs ca) {
             if constexpr (KEEP) {
                 const float ra = s.rho_a, rb = s.rho_b;
                 float ea[VEC], eb[VEC], fa, fb;
-                fold_chunk_keep<VEC, REV>(s, a, b, c, first_elem, ea, eb);
+                fold_chunk_keep<ClusterFold, VEC, REV>(s, a, b, c, first_elem, ea, eb);
                 if (moved(ra, rb, fa, fb)) rescale_kept(kRegChunks, c, fa, fb);
                 lds_a[c - kRegSpan] = S::pack(ea);
                 lds_b[c - kRegSpan] = S::pack(eb);
             } else {
-                fold_chunk<VEC, REV>(s, a, b, c);
+                fold_chunk<ClusterFold, VEC, REV>(s, a, b, c);
             }
         }
 
@@ -312,7 +312,7 @@ void row_cluster_kernel(ClusterArgs ca) {
             const float a1[1] = {S::load1(row_a + rag_i)};
             const float b1[1] = {S::load1(row_b + rag_i)};
             const float ra = s.rho_a, rb = s.rho_b;
-            fold<1, REV>(s, a1, b1, a1[0], b1[0]);
+            fold<ClusterFold, 1, REV>(s, a1, b1, a1[0], b1[0]);
             rag_v = a1[0];
             if constexpr (KEEP) {
                 float fa, fb;

@@ -39,8 +39,19 @@ constexpr float kLog2e = 1.44269504088896340736f;
 #ifndef PPOW_RESCALE_GAP
 #define PPOW_RESCALE_GAP 8.0f
 #endif
-constexpr float kRowGap = PPOW_RESCALE_GAP;
-constexpr float kClusterGap = 24.0f;
+// How a kernel folds: its rescale gap, and whether a chunk's exponentials are added in a tree
+// before they reach the running partition sums (eight more live registers, which the cluster
+// kernel -- it keeps a slice of both rows in registers -- cannot spare).
+struct RowFold {
+    static constexpr float gap = PPOW_RESCALE_GAP;
+    static constexpr bool tree = true;
+    static constexpr bool double_log = true;    // log2(Z_a / Z_b) of the epilogue in double
+};
+struct ClusterFold {
+    static constexpr float gap = 24.0f;
+    static constexpr bool tree = false;
+    static constexpr bool double_log = false;   // (the software double logarithm is register-hungry)
+};
 #define PPOW_NEG_INF (-__builtin_huge_valf())
 
 #ifndef PPOW_ROW_NONTEMPORAL
@@ -111,10 +122,8 @@ struct LaneState {
     float rho_b, z_b, s2r;      // draft side (s2r only when the reverse divergence is wanted)
     float m_a;                  // exact maximum of the target logits this lane has seen
     int best;                   // body chunk in which m_a was first reached (-1: none yet)
-    float gap;                  // a reference moves when a chunk maximum exceeds it by more
 
-    __device__ __forceinline__ void reset(float rescale_gap) {
-        gap = rescale_gap;
+    __device__ __forceinline__ void reset() {
         rho_a = PPOW_NEG_INF; z_a = 0.f; s1 = 0.f; s2 = 0.f;
         rho_b = PPOW_NEG_INF; z_b = 0.f; s2r = 0.f;
         m_a = PPOW_NEG_INF; best = -1;
@@ -144,50 +153,52 @@ __device__ __forceinline__ void rebase_draft(LaneState &s, float new_rho) {
 // Fold VEC element pairs into the running sums (no argmax bookkeeping).  With KEEP the two
 // exponentials of every pair, 2^(a*log2e - rho_a) and 2^(b*log2e - rho_b) relative to the
 // references as they stand after this call, are handed back for a later pass.
-template <int VEC, bool REV, bool KEEP>
+template <class POLICY, int VEC, bool REV, bool KEEP>
 __device__ __forceinline__ void fold_impl(LaneState &s, const float (&a)[VEC], const float (&b)[VEC],
                                           float cma, float cmb, float *ea, float *eb_out) {
     const float ta_max = fmaf(cma, kLog2e, -s.rho_a);
     const float tb_max = fmaf(cmb, kLog2e, -s.rho_b);
-    if (fmaxf(ta_max, tb_max) > s.gap) {            // rare: the reference lags too far behind
-        if (ta_max > s.gap) rebase_target(s, cma * kLog2e);
-        if (tb_max > s.gap) rebase_draft(s, cmb * kLog2e);
+    if (fmaxf(ta_max, tb_max) > POLICY::gap) {      // rare: the reference lags too far behind
+        if (ta_max > POLICY::gap) rebase_target(s, cma * kLog2e);
+        if (tb_max > POLICY::gap) rebase_draft(s, cmb * kLog2e);
     }
     // The two partition sums carry the log-sum-exps, whose difference is what is left of the
-    // divergence of nearly identical rows: the chunk's exponentials are added in a tree and
-    // reach the running sum with one addition (same count of additions as adding them one by
-    // one, an eighth of the roundings against the large running sum).
+    // divergence of nearly identical rows: with POLICY::tree the chunk's exponentials are added
+    // in a tree and reach the running sum with one addition (same count of additions as adding
+    // them one by one, an eighth of the roundings against the large running sum).
     float za[VEC], zb[VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {
         const float t = fmaf(a[j], kLog2e, -s.rho_a);
         const float e = fast_exp2(t);
         const float d = a[j] - b[j];
-        za[j] = e;
+        if (POLICY::tree) za[j] = e; else s.z_a += e;
         s.s1 = fmaf(e, t, s.s1);
         s.s2 = fmaf(e, d, s.s2);
         const float tb = fmaf(b[j], kLog2e, -s.rho_b);
         const float eb = fast_exp2(tb);
-        zb[j] = eb;
+        if (POLICY::tree) zb[j] = eb; else s.z_b += eb;
         if (REV) s.s2r = fmaf(eb, -d, s.s2r);
         if (KEEP) { ea[j] = e; eb_out[j] = eb; }
     }
+    if (POLICY::tree) {
 #pragma unroll
-    for (int w = 1; w < VEC; w <<= 1) {
+        for (int w = 1; w < VEC; w <<= 1) {
 #pragma unroll
-        for (int j = 0; j + w < VEC; j += 2 * w) { za[j] += za[j + w]; zb[j] += zb[j + w]; }
+            for (int j = 0; j + w < VEC; j += 2 * w) { za[j] += za[j + w]; zb[j] += zb[j + w]; }
+        }
+        s.z_a += za[0];
+        s.z_b += zb[0];
     }
-    s.z_a += za[0];
-    s.z_b += zb[0];
 }
 
-template <int VEC, bool REV>
+template <class POLICY, int VEC, bool REV>
 __device__ __forceinline__ void fold(LaneState &s, const float (&a)[VEC], const float (&b)[VEC],
                                      float cma, float cmb) {
-    fold_impl<VEC, REV, false>(s, a, b, cma, cmb, nullptr, nullptr);
+    fold_impl<POLICY, VEC, REV, false>(s, a, b, cma, cmb, nullptr, nullptr);
 }
 
-template <int VEC, bool REV>
+template <class POLICY, int VEC, bool REV>
 __device__ __forceinline__ void fold_chunk(LaneState &s, const float (&a)[VEC],
                                            const float (&b)[VEC], int chunk) {
     float cma = a[0], cmb = b[0];
@@ -198,13 +209,13 @@ __device__ __forceinline__ void fold_chunk(LaneState &s, const float (&a)[VEC],
     }
     s.best = (cma > s.m_a) ? chunk : s.best;       // strict: the first chunk keeps a tie
     s.m_a = fmaxf(s.m_a, cma);
-    fold<VEC, REV>(s, a, b, cma, cmb);
+    fold<POLICY, VEC, REV>(s, a, b, cma, cmb);
 }
 
 // As fold_chunk, but the raw logits will not be looked at again: the exponentials are kept in
 // their place (ea, eb), and the position of the lane's maximum is tracked to the element
 // (first_elem = chunk * VEC + first j of the chunk that reaches the chunk maximum).
-template <int VEC, bool REV>
+template <class POLICY, int VEC, bool REV>
 __device__ __forceinline__ void fold_chunk_keep(LaneState &s, const float (&a)[VEC],
                                                 const float (&b)[VEC], int chunk, int &first_elem,
                                                 float (&ea)[VEC], float (&eb)[VEC]) {
@@ -221,7 +232,7 @@ __device__ __forceinline__ void fold_chunk_keep(LaneState &s, const float (&a)[V
     s.best = better ? chunk : s.best;
     first_elem = better ? chunk * VEC + jf : first_elem;
     s.m_a = fmaxf(s.m_a, cma);
-    fold_impl<VEC, REV, true>(s, a, b, cma, cmb, ea, eb);
+    fold_impl<POLICY, VEC, REV, true>(s, a, b, cma, cmb, ea, eb);
 }
 
 // Pass-2 contribution of VEC pairs from kept exponentials: scale_a = 2^(rho_a - lam_a) etc.
@@ -372,7 +383,7 @@ __device__ __forceinline__ DraftedToken load_drafted_token(const RowArgs &args, 
     return d;
 }
 
-template <int DTYPE>
+template <int DTYPE, class POLICY>
 __device__ __forceinline__ void finish_row(const RowArgs &args, int64_t row, const RowTotals &t,
                                            float expected, const DraftedToken &drafted) {
     const float log2_za = fast_log2(t.z_a);
@@ -381,8 +392,11 @@ __device__ __forceinline__ void finish_row(const RowArgs &args, int64_t row, con
     const float ln2p = static_cast<float>(ln2p_d);
     const double inv_za = 1.0 / static_cast<double>(t.z_a);
     const double entropy = ln2p_d * (static_cast<double>(log2_za) - t.s1 * inv_za);
+    const double log2_ratio_z = POLICY::double_log
+        ? log2(static_cast<double>(t.z_a) / static_cast<double>(t.z_b))
+        : static_cast<double>(fast_log2(t.z_a / t.z_b));
     const double lse_diff = ln2p_d * ((static_cast<double>(t.ref_a) - static_cast<double>(t.ref_b)) +
-                                      log2(static_cast<double>(t.z_a) / static_cast<double>(t.z_b)));
+                                      log2_ratio_z);
     const float kl = fmaxf(static_cast<float>(t.s2 * inv_za - lse_diff), 0.f);
     float conf = static_cast<float>(1.0 - entropy * args.inv_ln_V);
     conf = fminf(fmaxf(conf, 0.f), 1.f);

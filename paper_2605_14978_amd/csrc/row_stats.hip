@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     const raw4 *pb = reinterpret_cast<const raw4 *>(row_b + head);
 
     LaneState s;
-    s.reset(kRowGap);
+    s.reset();
 
     // Prologue: every lane's first chunk, which also gives the wavefront its starting references.
     {
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
             first_b = chunk_max<VEC>(b);
         }
         start_reference(s, first_a, first_b);
-        if (tid < nchunks) fold_chunk<VEC, REV>(s, a, b, tid);
+        if (tid < nchunks) fold_chunk<RowFold, VEC, REV>(s, a, b, tid);
     }
 
     int c = tid + kThreads;
@@ -80,14 +80,14 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
             float a[VEC], b[VEC];
             S::unpack(ra[u], a);
             S::unpack(rb[u], b);
-            fold_chunk<VEC, REV>(s, a, b, c + u * kThreads);
+            fold_chunk<RowFold, VEC, REV>(s, a, b, c + u * kThreads);
         }
     }
     for (; c < nchunks; c += kThreads) {
         float a[VEC], b[VEC];
         S::unpack(load_chunk<!SECOND>(pa + c), a);
         S::unpack(load_chunk<!SECOND>(pb + c), b);
-        fold_chunk<VEC, REV>(s, a, b, c);
+        fold_chunk<RowFold, VEC, REV>(s, a, b, c);
     }
 
     // Ragged ends: fewer than kRowAlign bytes of elements before the vector body and at most
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
         rag_i = (tid < head) ? tid : tail_begin + (tid - head);
         const float a1[1] = {S::load1(row_a + rag_i)};
         const float b1[1] = {S::load1(row_b + rag_i)};
-        fold<1, REV>(s, a1, b1, a1[0], b1[0]);
+        fold<RowFold, 1, REV>(s, a1, b1, a1[0], b1[0]);
         rag_v = a1[0];
     }
 
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
         for (int w = 1; w < kWaves; ++w) expected += sh_f[w][5];
     }
 
-    if (tid == 0) finish_row<DTYPE>(args, row, t, expected, load_drafted_token<DTYPE>(args, row));
+    if (tid == 0) finish_row<DTYPE, RowFold>(args, row, t, expected, load_drafted_token<DTYPE>(args, row));
 }
 
 template <int DTYPE, bool SECOND>
