@@ -677,6 +677,36 @@ def test_select_matches_full_sort(B, M):
     check_selection(s.to(DEV), M)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_select_random_shapes_cover_every_kernel_and_sort_width(seed):
+    """Seeded random (B, M): register-resident selection with 4 / 16 / 32 composites per thread,
+    sorts of 2 / 4 / 8 composites per thread, slices with a ragged last one, and the general
+    kernel; scores with heavy ties, negative values and a narrow range."""
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.choice([rng.integers(1, 5000), rng.integers(5000, 33000), rng.integers(33000, 200000)]))
+    M = int(rng.choice([1, rng.integers(1, min(B, 2048) + 1), rng.integers(1, min(B, 8192) + 1),
+                        rng.integers(1, B + 1)]))
+    kind = seed % 3
+    g = torch.Generator().manual_seed(seed)
+    if kind == 0:
+        s = torch.rand(B, generator=g) * 0.01 + 0.9                 # one exponent, crowded digits
+    elif kind == 1:
+        s = torch.randint(0, 7, (B,), generator=g).float() - 3.0    # seven distinct values: ties
+    else:
+        s = torch.randn(B, generator=g) * torch.rand(B, generator=g).pow(8) * 1e3   # wide range
+    check_selection(s.to(DEV), M)
+
+
+@pytest.mark.parametrize("B,M", [(30000, 3000), (100000, 4096), (49153, 2049), (32768, 8192),
+                                 (32769, 1), (180000, 700), (50000, 50)])
+def test_select_shapes_at_the_kernel_boundaries(B, M):
+    g = torch.Generator().manual_seed(B ^ M)
+    s = torch.rand(B, generator=g)
+    s[torch.randint(0, B, (B // 7,), generator=g)] = 0.5
+    check_selection(s.to(DEV), M)
+    check_selection(torch.full((B,), 0.25, device=DEV), M)         # all equal: the M lowest indices
+
+
 def test_select_tie_at_the_boundary_prefers_lower_indices():
     s = torch.zeros(5000)
     s[::7] = 1.0                                   # 715 ones; the rest tie at zero
