@@ -84,6 +84,16 @@ def test_ragged_vocabulary_sizes(V, dtype):
     _check(d, V, M=2)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("expected_accept", [False, True])
+def test_rows_of_two_million_logits(dtype, expected_accept):
+    """Rows far longer than any benchmark vocabulary (and not a multiple of the 128-bit chunk):
+    thousands of chunks per lane, and more than any set of cooperating workgroups keeps on chip."""
+    V = 2_000_003
+    d = _random_inputs(2, 2, V, dtype, seed=77, sigma=0.5)
+    _check(d, V, expected_accept=expected_accept, M=1)
+
+
 @pytest.mark.parametrize("K", [1, 2, 5, 16, 17, 33, 64])
 def test_window_lengths(K):
     d = _random_inputs(9, K, 515, torch.float32, seed=100 + K, sigma=0.3)
