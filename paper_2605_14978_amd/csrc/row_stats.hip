@@ -20,6 +20,27 @@ constexpr int kThreads = PPOW_ROW_THREADS;
 constexpr int kWaves = kThreads / 64;
 constexpr int kUnroll = PPOW_ROW_UNROLL;
 
+// Tuning build (PPOW_ROW_TRACE=1): thread 0 records when its workgroup began and ended (100 MHz
+// clock) and where it ran (hardware id, XCD), for the first 40 000 rows, in the part of the
+// scratch in front of the records that this kernel does not use (bytes 4096 .. 4096 + 20 * 40000
+// of the workspace).
+#ifndef PPOW_ROW_TRACE
+#define PPOW_ROW_TRACE 0
+#endif
+#if PPOW_ROW_TRACE
+__device__ __forceinline__ void trace_row(const RowArgs &args, int64_t row, unsigned long long begin) {
+    if (row >= 40000) return;
+    char *base = reinterpret_cast<char *>(args.records) - kClusterScratchBytes + 4096;
+    unsigned long long *when = reinterpret_cast<unsigned long long *>(base);
+    when[2 * row] = begin;
+    when[2 * row + 1] = wall_clock64();
+    unsigned hw, xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    reinterpret_cast<unsigned *>(base + 16 * 40000)[row] = (hw & 0xffffu) | (xcc << 16);
+}
+#endif
+
 template <int DTYPE, bool SECOND, bool REV>
 __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     using S = Storage<DTYPE>;
@@ -34,6 +55,9 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     const int wave = tid >> 6;
     const int64_t row = blockIdx.x;
     const int V = static_cast<int>(args.V);
+#if PPOW_ROW_TRACE
+    const unsigned long long trace_begin = wall_clock64();
+#endif
 
     const elem *row_a = static_cast<const elem *>(args.target) + row * args.V;
     const elem *row_b = static_cast<const elem *>(args.draft) + row * args.V;
@@ -196,6 +220,9 @@ __global__ __launch_bounds__(kThreads) void row_stats_kernel(RowArgs args) {
     }
 
     if (tid == 0) finish_row<DTYPE, RowFold>(args, row, t, expected, load_drafted_token<DTYPE>(args, row));
+#if PPOW_ROW_TRACE
+    if (tid == 0) trace_row(args, row, trace_begin);
+#endif
 }
 
 template <int DTYPE, bool SECOND>

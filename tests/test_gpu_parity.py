@@ -94,6 +94,26 @@ def test_rows_of_two_million_logits(dtype, expected_accept):
     _check(d, V, expected_accept=expected_accept, M=1)
 
 
+@pytest.mark.parametrize("dtype,V", [(torch.float32, 1030), (torch.bfloat16, 2051), (torch.float32, 128)])
+def test_more_rows_than_resident_workgroups(dtype, V):
+    """Several times more row pairs than the device holds workgroups at once, also when the same
+    buffers are used again: every row is written by every call (outputs start out poisoned)."""
+    B, K = 2300, 5
+    d = _random_inputs(B, K, V, dtype, seed=V, sigma=0.6)
+    gpu, ref = _check(d, V, M=100)
+    assert ppow.last_row_kernel() == "row"
+    # the same call again into outputs that hold NaN: a row nobody claimed would keep it
+    buf = ppow.ScoreBuffers(B, K, V, ppow.PPOW_BF16 if dtype == torch.bfloat16 else ppow.PPOW_F32, DEV,
+                            ("kl", "confidence"))
+    for _ in range(3):
+        buf.kl.fill_(float("nan"))
+        buf.adaw_score.fill_(float("nan"))
+        ppow.ppow_score_windows(d["draft_logits"], d["target_logits"], d["draft_tokens"], d["uniforms"],
+                                cost_ratio=0.05, buffers=buf)
+        torch.cuda.synchronize()
+        assert torch.equal(buf.kl, gpu.kl) and torch.equal(buf.adaw_score, gpu.adaw_score)
+
+
 @pytest.mark.parametrize("K", [1, 2, 5, 16, 17, 33, 64])
 def test_window_lengths(K):
     d = _random_inputs(9, K, 515, torch.float32, seed=100 + K, sigma=0.3)
