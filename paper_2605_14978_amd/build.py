@@ -34,5 +34,28 @@ def build(verbose: bool = False, defines=(), output: str = LIBRARY) -> str:
     return output
 
 
+def sanitizer_runtime():
+    """Path of clang's shared AddressSanitizer runtime beside hipcc's compiler, or None."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = subprocess.run([hipcc, "-print-file-name=libclang_rt.asan-x86_64.so"],
+                         capture_output=True, text=True)
+    path = out.stdout.strip()
+    return path if os.path.isabs(path) and os.path.exists(path) else None
+
+
+def build_host_sanitized(output: str) -> str:
+    """The same library with AddressSanitizer + UndefinedBehaviorSanitizer on its HOST code only
+    (argument checks, workspace arithmetic, launch set-up); device code is built as usual.  For
+    CPU-side tests: load it in a process that has sanitizer_runtime() preloaded."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + ["-O1", "-g", "-shared-libsan"]
+    for f in ("-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"):
+        flags += ["-Xarch_host", f]
+    cmd = [hipcc] + flags + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    cmd += [os.path.join(CSRC, s) for s in SOURCES] + ["-o", output]
+    subprocess.run(cmd, check=True, cwd=HERE)
+    return output
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
