@@ -195,6 +195,9 @@ __global__ __launch_bounds__(kThreads) void select_general_kernel(const float *_
 
 // Optional phase timing for tuning (off in the product build): thread 0 of workgroup 0 leaves
 // shader-clock readings at the phase boundaries of the resident kernel.
+#ifndef PPOW_SELECT_FEW_DIGITS
+#define PPOW_SELECT_FEW_DIGITS 8
+#endif
 #ifndef PPOW_SELECT_TIMING
 #define PPOW_SELECT_TIMING 0
 #endif
@@ -204,6 +207,8 @@ __device__ long long g_select_ticks[8];
 #else
 #define PPOW_SELECT_TICK(i) do { } while (0)
 #endif
+
+constexpr uint32_t kFewDigits = PPOW_SELECT_FEW_DIGITS;   // digit span counted with ballots
 
 struct SelectShared {
     uint32_t hist[2][256];          // double-buffered by pass: the next pass's bins are cleared
@@ -231,12 +236,19 @@ __device__ __forceinline__ uint64_t lane_xor(uint64_t x) {
     const uint32_t hi = lane_xor<D>(static_cast<uint32_t>(x >> 32));
     return (static_cast<uint64_t>(hi) << 32) | lo;
 }
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
-    x += lane_xor<1>(x); x += lane_xor<2>(x); x += lane_xor<4>(x); x += lane_xor<8>(x);
-    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 0)) +
-           static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 16)) +
-           static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 32)) +
-           static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 48));
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+    x = min(x, lane_xor<1>(x)); x = min(x, lane_xor<2>(x)); x = min(x, lane_xor<4>(x)); x = min(x, lane_xor<8>(x));
+    return min(min(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 0)),
+                   static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 16))),
+               min(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 32)),
+                   static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 48))));
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+    x = max(x, lane_xor<1>(x)); x = max(x, lane_xor<2>(x)); x = max(x, lane_xor<4>(x)); x = max(x, lane_xor<8>(x));
+    return max(max(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 0)),
+                   static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 16))),
+               max(static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 32)),
+                   static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(x), 48))));
 }
 
 // Inclusive sum over lanes 0..l: four shifts inside each row of 16 lanes, then the last lane
@@ -276,28 +288,33 @@ __device__ __forceinline__ uint64_t radix_select(const uint64_t (&key)[E], uint3
         }
         uint32_t *hist = sh.hist[pass & 1];
         if (tid < 256) sh.hist[(pass & 1) ^ 1][tid] = 0;          // for the next pass
-        // Scores crowd into few leading digits: a wavefront whose matching composites all share
-        // one digit (the rule in the first passes) counts them with a single LDS atomic; one
-        // with mixed digits (the rule later, when they spread over the bins) adds them one by one.
-        uint32_t first_digit = 0xffffffffu, mine = 0;
-        bool same = true;
+        // Scores crowd into few leading digits: LDS atomics on one bin are served one lane at a
+        // time, so a wavefront whose matching composites span few digits (the rule in the first
+        // passes) counts them digit by digit with ballots and adds each count with one atomic;
+        // one whose digits are spread (the rule later) adds its composites one by one.
+        uint32_t lo = 256u, hi = 0u;
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             const uint64_t c = key[e];
             const bool match = c != 0 && (c & prefix_mask) == prefix;
             const uint32_t digit = static_cast<uint32_t>(c >> shift) & 0xffu;
-            same = same && (!match || first_digit == 0xffffffffu || digit == first_digit);
-            first_digit = (match && first_digit == 0xffffffffu) ? digit : first_digit;
-            mine += match ? 1u : 0u;
+            lo = match ? min(lo, digit) : lo;
+            hi = match ? max(hi, digit) : hi;
         }
-        const unsigned long long have = __ballot(mine != 0);
-        if (have) {
-            const int leader = __ffsll(static_cast<long long>(have)) - 1;
-            const uint32_t d0 = static_cast<uint32_t>(
-                __builtin_amdgcn_readlane(static_cast<int>(first_digit), leader));
-            if (__all(mine == 0 || (same && first_digit == d0))) {
-                const uint32_t total = wave_sum_u32(mine);
-                if (lane == 0) atomicAdd(&hist[d0], total);
+        const uint32_t wave_lo = wave_min_u32(lo), wave_hi = wave_max_u32(hi);
+        if (wave_lo <= wave_hi) {                                   // some composite matches
+            if (wave_hi - wave_lo < kFewDigits) {
+                for (uint32_t d = wave_lo; d <= wave_hi; ++d) {     // the same trip count in every lane
+                    uint32_t count = 0;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const uint64_t c = key[e];
+                        const bool here = c != 0 && (c & prefix_mask) == prefix &&
+                                          (static_cast<uint32_t>(c >> shift) & 0xffu) == d;
+                        count += static_cast<uint32_t>(__popcll(__ballot(here)));
+                    }
+                    if (lane == 0 && count != 0) atomicAdd(&hist[d], count);
+                }
             } else {
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
